@@ -1,0 +1,139 @@
+/*
+ * bwta.h -- C ABI of the BWTA (Binary Weights & Ternary Activations) linear-layer
+ * hot path for AMD MI355X (gfx950).
+ *
+ * The layer is the paper's BWTA linear equation ("Basic Layers for Linear and
+ * MatMul"):   linear(A) = s_W * s_A * ( sign(W) (x) ternary(A^T, s_A) ),
+ * evaluated the way its kernel section describes: binary weights are packed to
+ * one bit each ahead of time, activations are ternarised and packed to two bit
+ * planes at run time, the product is an exact integer contraction with int32
+ * accumulation, and results are cast back to fp16 before they leave the kernel.
+ *
+ * Conventions shared by every call
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *     allocates nothing, frees nothing, keeps no pointer after the call returns
+ *     and never synchronises: work is enqueued on `stream` (a hipStream_t passed
+ *     as void*; NULL is the null stream) and the call returns at once.
+ *   - Matrices are row-major.  Activations are [M, K] (M tokens), weights are
+ *     [N, K] (N output channels), results are [M, N]; the paper writes the same
+ *     numbers as W (x) A^T, i.e. transposed.
+ *   - Packed planes: element k of a row sits in 32-bit word k/32 at bit k%32
+ *     (least significant bit first).  Rows hold bwta_plane_row_words(K) words,
+ *     i.e. they are padded with ZERO bits to a multiple of 128 bits, and plane
+ *     base pointers must be 16-byte aligned.  Polarity follows the paper's
+ *     bitpack: a negative value is bit 1, a positive value bit 0.  A ternary
+ *     operand uses two planes: `mask` (value != 0) and `sign` (value < 0, always
+ *     a subset of mask); the paper's A- plane is `sign`, its A+ plane is
+ *     mask ^ sign.
+ *   - Scales are fp16.  scale_mode says how a scale pointer is read:
+ *     BWTA_SCALE_NONE (pointer ignored, scale 1), BWTA_SCALE_SCALAR (one value),
+ *     BWTA_SCALE_VECTOR (one per token for s_a, one per output channel for s_w).
+ *   - Return value: BWTA_OK, or a negative BWTA_ERR_* code.  Argument errors are
+ *     detected on the host before anything is enqueued; BWTA_ERR_HIP means a
+ *     launch was rejected by the runtime (see bwta_last_hip_error()).
+ */
+#ifndef BWTA_H
+#define BWTA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef void *bwta_stream_t; /* a hipStream_t */
+
+enum {
+    BWTA_OK = 0,
+    BWTA_ERR_NULL = -1,        /* a required pointer is NULL                               */
+    BWTA_ERR_SHAPE = -2,       /* M, N or K < 0, K == 0 with M,N > 0, or a leading dim < row */
+    BWTA_ERR_ALIGN = -3,       /* a plane / output pointer or leading dimension is misaligned */
+    BWTA_ERR_UNSUPPORTED = -4, /* unknown dtype, scale mode or path                        */
+    BWTA_ERR_WORKSPACE = -5,   /* workspace NULL or smaller than bwta_workspace_bytes()    */
+    BWTA_ERR_HIP = -6          /* the HIP runtime reported an error at launch              */
+};
+
+enum { BWTA_DTYPE_FP16 = 0, BWTA_DTYPE_INT8 = 1 };
+enum { BWTA_SCALE_NONE = 0, BWTA_SCALE_SCALAR = 1, BWTA_SCALE_VECTOR = 2 };
+/* Which contraction kernel bwta_gemm / bwta_linear use.  AUTO picks per shape regime from
+ * measurements on MI355X; the other two force the wave64 popcount kernels or the int8
+ * matrix-core (MFMA) kernel.  All three produce identical bits. */
+enum { BWTA_PATH_AUTO = 0, BWTA_PATH_POPC = 1, BWTA_PATH_MFMA = 2 };
+
+/* Words per packed row: 4 * ceil(K / 128).  Returns 0 for K <= 0. */
+int64_t bwta_plane_row_words(int K);
+
+/* Bytes of caller-provided scratch that bwta_linear (and bwta_gemm) need for this shape;
+ * a pure function of (M, N, K), 256-byte granular, 0 only if M, N or K is 0. */
+size_t bwta_workspace_bytes(int M, int N, int K);
+
+/*
+ * Ternarise and bit-pack activations (the paper's "Ternary Function" equation, packed as in
+ * "Instruction-level Parallel Bitpack" / ternary bitpack).
+ *   A        a_dtype FP16: fp16 [M, lda]; element -> +1 if a >= 0.5*s, -1 if a < -0.5*s,
+ *            else 0 (so a == +0.5*s gives +1 and a == -0.5*s gives 0, as printed).  The
+ *            comparison is exact (no division).  NaN gives 0, +-Inf gives +-1.  A scale that is
+ *            not finite and > 0 ternarises its row to 0.
+ *            a_dtype INT8: int8 [M, lda] already ternary; >0 -> +1, <0 -> -1 (scale unused).
+ *   lda      leading dimension in elements, >= K.
+ *   s_a      fp16 scale(s) per scale_mode (per token for VECTOR); may be NULL with NONE.
+ *   mask, sign   out, u32 [M, row_words] each, pad bits written as 0.
+ *   nnz      out, optional (NULL to skip): int32 [M], nonzeros per token.
+ */
+int bwta_quantize_pack_act(const void *A, int a_dtype, int64_t lda, const void *s_a,
+                           int scale_mode, int M, int K, uint32_t *mask, uint32_t *sign,
+                           int32_t *nnz, bwta_stream_t stream);
+
+/*
+ * Sign-pack binary weights (the paper's sign equation in "Binary Functions"; done once, before
+ * inference).  W is fp16 [N, ldw] (bit = 0 if w >= 0, so -0.0 -> bit 0; otherwise, NaN
+ * included, bit 1) or int8 [N, ldw] (bit = w < 0).  wsign: out, u32 [N, row_words].
+ * Mean-centring and the weight scale are the caller's business: pass W - mean(W) and keep s_W.
+ */
+int bwta_pack_weights(const void *W, int w_dtype, int64_t ldw, int N, int K, uint32_t *wsign,
+                      bwta_stream_t stream);
+
+/*
+ * BWTA matrix product with fused scale epilogue (Case 1 of the paper's "Comprehensive
+ * Computational Implementations", the xor-based BWTA MatMul):
+ *   acc[m, n] = sum_k t[m,k] * w[n,k] = popc(mask_m) - 2 * popc(mask_m & (sign_m ^ wsign_n))
+ *   out[m, n] = fp16( s_w[n] * s_a[m] * acc[m, n] )   exact product, one rounding (nearest even)
+ *   mask, sign  u32 [M, row_words]; sign bits under a zero mask bit are ignored.
+ *   wsign       u32 [N, row_words].
+ *   acc         optional out, int32 [M, N] dense (leading dimension N).
+ *   out         optional out, fp16 [M, ldo], ldo >= N.  At least one of acc / out.
+ *   workspace   scratch of at least bwta_workspace_bytes(M, N, K) bytes, 256-byte aligned;
+ *               contents undefined afterwards.  Calls that share a workspace must not overlap.
+ */
+int bwta_gemm(const uint32_t *mask, const uint32_t *sign, const uint32_t *wsign, int M, int N,
+              int K, const void *s_a, int a_scale_mode, const void *s_w, int w_scale_mode,
+              int32_t *acc, void *out, int64_t ldo, void *workspace, size_t workspace_bytes,
+              bwta_stream_t stream);
+
+/*
+ * The whole layer on fp16 activations: ternarise + pack + product + scale epilogue
+ * (the BWTA linear equation end to end).  A fp16 [M, lda]; wsign from bwta_pack_weights;
+ * out fp16 [M, ldo].  s_a is used both as the ternarisation scale and in the epilogue.
+ */
+int bwta_linear(const void *A, int64_t lda, const void *s_a, int a_scale_mode,
+                const uint32_t *wsign, const void *s_w, int w_scale_mode, int M, int N, int K,
+                void *out, int64_t ldo, void *workspace, size_t workspace_bytes,
+                bwta_stream_t stream);
+
+/* Human-readable text for a return code (static storage). */
+const char *bwta_strerror(int code);
+/* hipError_t value behind the calling thread's most recent BWTA_ERR_HIP (0 if none). */
+int bwta_last_hip_error(void);
+/* Select the contraction kernel family (process-wide).  Returns BWTA_OK or UNSUPPORTED. */
+int bwta_set_path(int path);
+int bwta_get_path(void);
+/* Which family AUTO resolves to for a shape: BWTA_PATH_POPC or BWTA_PATH_MFMA. */
+int bwta_auto_path(int M, int N, int K);
+/* Library version, major * 100 + minor. */
+int bwta_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BWTA_H */

@@ -1,0 +1,158 @@
+"""Thin ctypes binding of ``csrc/libbwta.so`` (the C ABI declared in ``include/bwta.h``).
+
+Argument marshalling only: every step of the path runs in the HIP kernels.  Tensors are
+torch CUDA tensors used as device buffers; the current torch stream is passed through.
+Importing this module without the compiled library raises -- there is no fallback.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "csrc", "libbwta.so")
+
+OK = 0
+ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = -1, -2, -3, -4, -5, -6
+DTYPE_FP16, DTYPE_INT8 = 0, 1
+SCALE_NONE, SCALE_SCALAR, SCALE_VECTOR = 0, 1, 2
+PATH_AUTO, PATH_POPC, PATH_MFMA = 0, 1, 2
+
+EXPORTS = ["bwta_plane_row_words", "bwta_workspace_bytes", "bwta_quantize_pack_act",
+           "bwta_pack_weights", "bwta_gemm", "bwta_linear", "bwta_strerror", "bwta_last_hip_error",
+           "bwta_set_path", "bwta_get_path", "bwta_auto_path", "bwta_version"]
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        "%s is missing: build it first (python -c 'import __graft_entry__ as g; g.build()' "
+        "or python paper_2604_03957_amd/build.py); there is no CPU fallback" % LIB_PATH)
+
+_lib = ctypes.CDLL(LIB_PATH)
+_c = ctypes
+_P = _c.c_void_p
+_lib.bwta_plane_row_words.restype = _c.c_int64
+_lib.bwta_plane_row_words.argtypes = [_c.c_int]
+_lib.bwta_workspace_bytes.restype = _c.c_size_t
+_lib.bwta_workspace_bytes.argtypes = [_c.c_int, _c.c_int, _c.c_int]
+_lib.bwta_quantize_pack_act.restype = _c.c_int
+_lib.bwta_quantize_pack_act.argtypes = [_P, _c.c_int, _c.c_int64, _P, _c.c_int, _c.c_int, _c.c_int,
+                                        _P, _P, _P, _P]
+_lib.bwta_pack_weights.restype = _c.c_int
+_lib.bwta_pack_weights.argtypes = [_P, _c.c_int, _c.c_int64, _c.c_int, _c.c_int, _P, _P]
+_lib.bwta_gemm.restype = _c.c_int
+_lib.bwta_gemm.argtypes = [_P, _P, _P, _c.c_int, _c.c_int, _c.c_int, _P, _c.c_int, _P, _c.c_int,
+                           _P, _P, _c.c_int64, _P, _c.c_size_t, _P]
+_lib.bwta_linear.restype = _c.c_int
+_lib.bwta_linear.argtypes = [_P, _c.c_int64, _P, _c.c_int, _P, _P, _c.c_int, _c.c_int, _c.c_int,
+                             _c.c_int, _P, _c.c_int64, _P, _c.c_size_t, _P]
+_lib.bwta_strerror.restype = _c.c_char_p
+_lib.bwta_strerror.argtypes = [_c.c_int]
+_lib.bwta_last_hip_error.restype = _c.c_int
+_lib.bwta_set_path.restype = _c.c_int
+_lib.bwta_set_path.argtypes = [_c.c_int]
+_lib.bwta_get_path.restype = _c.c_int
+_lib.bwta_auto_path.restype = _c.c_int
+_lib.bwta_auto_path.argtypes = [_c.c_int, _c.c_int, _c.c_int]
+_lib.bwta_version.restype = _c.c_int
+
+
+class BwtaError(RuntimeError):
+    def __init__(self, code):
+        self.code = code
+        msg = _lib.bwta_strerror(code).decode()
+        if code == ERR_HIP:
+            msg += " [hipError %d]" % _lib.bwta_last_hip_error()
+        super().__init__("bwta error %d: %s" % (code, msg))
+
+
+def raw():
+    """The ctypes library handle, for tests that probe error codes directly."""
+    return _lib
+
+
+def _check(code):
+    if code != OK:
+        raise BwtaError(code)
+
+
+def _ptr(x):
+    """Device pointer of a torch tensor, a raw integer address, or None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def _stream(stream):
+    if stream is not None:
+        return stream if isinstance(stream, int) else stream.cuda_stream
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _mode(s, mode):
+    if mode is not None:
+        return mode
+    if s is None:
+        return SCALE_NONE
+    return SCALE_SCALAR if s.numel() == 1 else SCALE_VECTOR
+
+
+def plane_row_words(K):
+    return int(_lib.bwta_plane_row_words(K))
+
+
+def workspace_bytes(M, N, K):
+    return int(_lib.bwta_workspace_bytes(M, N, K))
+
+
+def strerror(code):
+    return _lib.bwta_strerror(code).decode()
+
+
+def set_path(path):
+    _check(_lib.bwta_set_path(path))
+
+
+def get_path():
+    return int(_lib.bwta_get_path())
+
+
+def auto_path(M, N, K):
+    return int(_lib.bwta_auto_path(M, N, K))
+
+
+def version():
+    return int(_lib.bwta_version())
+
+
+def bwta_quantize_pack_act(A, s_a, mask, sign, nnz=None, *, M, K, lda=None, a_dtype=DTYPE_FP16,
+                           scale_mode=None, stream=None):
+    lda = K if lda is None else lda
+    _check(_lib.bwta_quantize_pack_act(_ptr(A), a_dtype, lda, _ptr(s_a), _mode(s_a, scale_mode), M, K,
+                                       _ptr(mask), _ptr(sign), _ptr(nnz), _stream(stream)))
+
+
+def bwta_pack_weights(W, wsign, *, N, K, ldw=None, w_dtype=DTYPE_INT8, stream=None):
+    ldw = K if ldw is None else ldw
+    _check(_lib.bwta_pack_weights(_ptr(W), w_dtype, ldw, N, K, _ptr(wsign), _stream(stream)))
+
+
+def bwta_gemm(mask, sign, wsign, s_a, s_w, acc, out, workspace, *, M, N, K, ldo=None,
+              a_scale_mode=None, w_scale_mode=None, workspace_bytes=None, stream=None):
+    ldo = N if ldo is None else ldo
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None or isinstance(workspace, int) else workspace.numel() * workspace.element_size()
+    _check(_lib.bwta_gemm(_ptr(mask), _ptr(sign), _ptr(wsign), M, N, K, _ptr(s_a), _mode(s_a, a_scale_mode),
+                          _ptr(s_w), _mode(s_w, w_scale_mode), _ptr(acc), _ptr(out), ldo,
+                          _ptr(workspace), workspace_bytes, _stream(stream)))
+
+
+def bwta_linear(A, s_a, wsign, s_w, out, workspace, *, M, N, K, lda=None, ldo=None, a_scale_mode=None,
+                w_scale_mode=None, workspace_bytes=None, stream=None):
+    lda = K if lda is None else lda
+    ldo = N if ldo is None else ldo
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None or isinstance(workspace, int) else workspace.numel() * workspace.element_size()
+    _check(_lib.bwta_linear(_ptr(A), lda, _ptr(s_a), _mode(s_a, a_scale_mode), _ptr(wsign), _ptr(s_w),
+                            _mode(s_w, w_scale_mode), M, N, K, _ptr(out), ldo, _ptr(workspace),
+                            workspace_bytes, _stream(stream)))

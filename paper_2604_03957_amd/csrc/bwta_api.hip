@@ -1,0 +1,176 @@
+// C ABI of libbwta.so: host-side argument validation and dispatch.  Every check happens before
+// anything is enqueued, so a bad call never touches the device.
+#include "../../include/bwta.h"
+
+#include <atomic>
+
+#include "bwta_internal.h"
+
+namespace {
+
+std::atomic<int> g_path{BWTA_PATH_AUTO};
+thread_local int t_last_hip_error = 0;
+
+inline bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int hip_result(hipError_t e)
+{
+    if (e == hipSuccess) return BWTA_OK;
+    t_last_hip_error = (int)e;
+    return BWTA_ERR_HIP;
+}
+
+bool scale_mode_ok(int mode) { return mode >= BWTA_SCALE_NONE && mode <= BWTA_SCALE_VECTOR; }
+
+size_t plane_bytes(int M, int K) { return round_up((size_t)M * (size_t)bwta_plane_row_words(K) * 4u, 256); }
+
+int resolve_path(int M, int N, int K)
+{
+    int p = g_path.load(std::memory_order_relaxed);
+    return p == BWTA_PATH_AUTO ? bwta_auto_path(M, N, K) : p;
+}
+
+int run_gemm(const bwta::GemmArgs &g, hipStream_t st)
+{
+    int path = resolve_path(g.M, g.N, g.K);
+    if (path == BWTA_PATH_MFMA && bwta::gemm_mfma_supported(g)) return hip_result(bwta::launch_gemm_mfma(g, st));
+    return hip_result(bwta::launch_gemm_popc(g, st));
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t bwta_plane_row_words(int K) { return K <= 0 ? 0 : 4 * (((int64_t)K + 127) / 128); }
+
+size_t bwta_workspace_bytes(int M, int N, int K)
+{
+    if (M <= 0 || N <= 0 || K <= 0) return 0;
+    return 2 * plane_bytes(M, K);  // mask + sign planes of bwta_linear
+}
+
+int bwta_quantize_pack_act(const void *A, int a_dtype, int64_t lda, const void *s_a, int scale_mode,
+                           int M, int K, uint32_t *mask, uint32_t *sign, int32_t *nnz,
+                           bwta_stream_t stream)
+{
+    if (a_dtype != BWTA_DTYPE_FP16 && a_dtype != BWTA_DTYPE_INT8) return BWTA_ERR_UNSUPPORTED;
+    if (!scale_mode_ok(scale_mode)) return BWTA_ERR_UNSUPPORTED;
+    if (M < 0 || K < 0 || (M > 0 && K == 0)) return BWTA_ERR_SHAPE;
+    if (M == 0) return BWTA_OK;
+    if (lda < K) return BWTA_ERR_SHAPE;
+    if (!A || !mask || !sign) return BWTA_ERR_NULL;
+    if (scale_mode != BWTA_SCALE_NONE && a_dtype == BWTA_DTYPE_FP16 && !s_a) return BWTA_ERR_NULL;
+    if (!aligned(mask, 16) || !aligned(sign, 16)) return BWTA_ERR_ALIGN;
+    if (a_dtype == BWTA_DTYPE_FP16 && !aligned(A, 2)) return BWTA_ERR_ALIGN;
+    if (s_a && !aligned(s_a, 2)) return BWTA_ERR_ALIGN;
+    if (nnz && !aligned(nnz, 4)) return BWTA_ERR_ALIGN;
+    bwta::ScaleArg sa{(const uint16_t *)s_a, s_a ? scale_mode : BWTA_SCALE_NONE};
+    return hip_result(bwta::launch_quantize_pack(A, a_dtype, lda, sa, M, K, mask, sign, nnz, (hipStream_t)stream));
+}
+
+int bwta_pack_weights(const void *W, int w_dtype, int64_t ldw, int N, int K, uint32_t *wsign,
+                      bwta_stream_t stream)
+{
+    if (w_dtype != BWTA_DTYPE_FP16 && w_dtype != BWTA_DTYPE_INT8) return BWTA_ERR_UNSUPPORTED;
+    if (N < 0 || K < 0 || (N > 0 && K == 0)) return BWTA_ERR_SHAPE;
+    if (N == 0) return BWTA_OK;
+    if (ldw < K) return BWTA_ERR_SHAPE;
+    if (!W || !wsign) return BWTA_ERR_NULL;
+    if (!aligned(wsign, 16)) return BWTA_ERR_ALIGN;
+    if (w_dtype == BWTA_DTYPE_FP16 && !aligned(W, 2)) return BWTA_ERR_ALIGN;
+    return hip_result(bwta::launch_pack_weights(W, w_dtype, ldw, N, K, wsign, (hipStream_t)stream));
+}
+
+static int check_gemm_common(int M, int N, int K, const void *s_a, int a_mode, const void *s_w, int w_mode,
+                             const void *out, int64_t ldo)
+{
+    if (!scale_mode_ok(a_mode) || !scale_mode_ok(w_mode)) return BWTA_ERR_UNSUPPORTED;
+    if (M < 0 || N < 0 || K < 0 || (M > 0 && N > 0 && K == 0)) return BWTA_ERR_SHAPE;
+    if (out && ldo < N) return BWTA_ERR_SHAPE;
+    if (a_mode != BWTA_SCALE_NONE && !s_a) return BWTA_ERR_NULL;
+    if (w_mode != BWTA_SCALE_NONE && !s_w) return BWTA_ERR_NULL;
+    if ((s_a && !aligned(s_a, 2)) || (s_w && !aligned(s_w, 2))) return BWTA_ERR_ALIGN;
+    if (out && !aligned(out, 2)) return BWTA_ERR_ALIGN;
+    return BWTA_OK;
+}
+
+int bwta_gemm(const uint32_t *mask, const uint32_t *sign, const uint32_t *wsign, int M, int N, int K,
+              const void *s_a, int a_scale_mode, const void *s_w, int w_scale_mode, int32_t *acc,
+              void *out, int64_t ldo, void *workspace, size_t workspace_bytes, bwta_stream_t stream)
+{
+    int rc = check_gemm_common(M, N, K, s_a, a_scale_mode, s_w, w_scale_mode, out, ldo);
+    if (rc != BWTA_OK) return rc;
+    if (M == 0 || N == 0) return BWTA_OK;
+    if (!mask || !sign || !wsign) return BWTA_ERR_NULL;
+    if (!acc && !out) return BWTA_ERR_NULL;
+    if (!aligned(mask, 16) || !aligned(sign, 16) || !aligned(wsign, 16)) return BWTA_ERR_ALIGN;
+    if (acc && !aligned(acc, 4)) return BWTA_ERR_ALIGN;
+    if (!workspace || workspace_bytes < bwta_workspace_bytes(M, N, K)) return BWTA_ERR_WORKSPACE;
+    if (!aligned(workspace, 256)) return BWTA_ERR_ALIGN;
+    bwta::GemmArgs g{mask, sign, wsign, M, N, K, (int)bwta_plane_row_words(K),
+                     {(const uint16_t *)s_a, s_a ? a_scale_mode : BWTA_SCALE_NONE},
+                     {(const uint16_t *)s_w, s_w ? w_scale_mode : BWTA_SCALE_NONE},
+                     acc, (uint16_t *)out, ldo};
+    return run_gemm(g, (hipStream_t)stream);
+}
+
+int bwta_linear(const void *A, int64_t lda, const void *s_a, int a_scale_mode, const uint32_t *wsign,
+                const void *s_w, int w_scale_mode, int M, int N, int K, void *out, int64_t ldo,
+                void *workspace, size_t workspace_bytes, bwta_stream_t stream)
+{
+    int rc = check_gemm_common(M, N, K, s_a, a_scale_mode, s_w, w_scale_mode, out, ldo);
+    if (rc != BWTA_OK) return rc;
+    if (M == 0 || N == 0) return BWTA_OK;
+    if (lda < K) return BWTA_ERR_SHAPE;
+    if (!A || !wsign || !out) return BWTA_ERR_NULL;
+    if (!aligned(A, 2) || !aligned(wsign, 16)) return BWTA_ERR_ALIGN;
+    if (!workspace || workspace_bytes < bwta_workspace_bytes(M, N, K)) return BWTA_ERR_WORKSPACE;
+    if (!aligned(workspace, 256)) return BWTA_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    uint32_t *mask = (uint32_t *)workspace;
+    uint32_t *sign = (uint32_t *)((char *)workspace + plane_bytes(M, K));
+    bwta::ScaleArg sa{(const uint16_t *)s_a, s_a ? a_scale_mode : BWTA_SCALE_NONE};
+    rc = hip_result(bwta::launch_quantize_pack(A, BWTA_DTYPE_FP16, lda, sa, M, K, mask, sign, nullptr, st));
+    if (rc != BWTA_OK) return rc;
+    bwta::GemmArgs g{mask, sign, wsign, M, N, K, (int)bwta_plane_row_words(K), sa,
+                     {(const uint16_t *)s_w, s_w ? w_scale_mode : BWTA_SCALE_NONE},
+                     nullptr, (uint16_t *)out, ldo};
+    return run_gemm(g, st);
+}
+
+const char *bwta_strerror(int code)
+{
+    switch (code) {
+    case BWTA_OK: return "ok";
+    case BWTA_ERR_NULL: return "a required pointer is NULL";
+    case BWTA_ERR_SHAPE: return "invalid shape or leading dimension";
+    case BWTA_ERR_ALIGN: return "misaligned pointer";
+    case BWTA_ERR_UNSUPPORTED: return "unsupported dtype, scale mode or path";
+    case BWTA_ERR_WORKSPACE: return "workspace missing or too small";
+    case BWTA_ERR_HIP: return "HIP runtime error at launch (see bwta_last_hip_error)";
+    default: return "unknown error code";
+    }
+}
+
+int bwta_last_hip_error(void) { return t_last_hip_error; }
+
+int bwta_set_path(int path)
+{
+    if (path != BWTA_PATH_AUTO && path != BWTA_PATH_POPC && path != BWTA_PATH_MFMA) return BWTA_ERR_UNSUPPORTED;
+    g_path.store(path, std::memory_order_relaxed);
+    return BWTA_OK;
+}
+
+int bwta_get_path(void) { return g_path.load(std::memory_order_relaxed); }
+
+int bwta_auto_path(int M, int N, int K)
+{
+    (void)N;
+    (void)K;
+    return M >= 16 ? BWTA_PATH_MFMA : BWTA_PATH_POPC;
+}
+
+int bwta_version(void) { return 1; }
+
+}  // extern "C"

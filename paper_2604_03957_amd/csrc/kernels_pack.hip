@@ -1,0 +1,205 @@
+// Ternarise + bit-pack activations, sign-pack weights (paper: "Ternary Function" and sign
+// equations; "Instruction-level Parallel Bitpack").  Bandwidth-bound streaming kernels: every
+// lane takes 8 consecutive elements with one 128-bit (fp16) or 64-bit (int8) load, turns them
+// into one byte per plane, and the four lanes of a quad assemble a 32-bit plane word.
+#include "bwta_internal.h"
+
+namespace bwta {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+// OR a per-lane byte into its quad's 32-bit word (lane q of the quad supplies byte q).
+__device__ __forceinline__ uint32_t quad_word(uint32_t byte, int lane)
+{
+    uint32_t v = byte << (8 * (lane & 3));
+    v |= __shfl_xor(v, 1);
+    v |= __shfl_xor(v, 2);
+    return v;
+}
+
+struct TernaryBits {
+    uint32_t nz, neg;
+};
+
+// 8 fp16 values against the exact thresholds +-h (h = 0.5 * s in fp32, exact).
+__device__ __forceinline__ TernaryBits ternary_bits_fp16(const uint16_t v[8], int nvalid, float h, bool ok)
+{
+    TernaryBits r{0u, 0u};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        float a = half_bits_to_float(v[i]);
+        bool pos = a >= h, neg = a < -h;  // NaN fails both
+        bool live = ok && (i < nvalid);
+        r.nz |= (uint32_t)(live && (pos || neg)) << i;
+        r.neg |= (uint32_t)(live && neg) << i;
+    }
+    return r;
+}
+
+template <int DTYPE>  // 0 = fp16 activations, 1 = int8 ternary activations
+__global__ __launch_bounds__(kThreads) void k_quantize_pack(const void *__restrict__ A, int64_t lda,
+                                                            ScaleArg s_a, int M, int K, int rw,
+                                                            uint32_t *__restrict__ mask,
+                                                            uint32_t *__restrict__ sign, int vec_ok)
+{
+    const int c8 = rw * 4;  // byte-groups (8 elements) per packed row, a multiple of 16
+    const int64_t total = (int64_t)M * c8;
+    const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (gid >= total) return;  // whole quads leave together (total % 4 == 0)
+    const int m = (int)(gid / c8);
+    const int c = (int)(gid - (int64_t)m * c8);
+    const int k0 = c * 8;
+    const int nvalid = K - k0 >= 8 ? 8 : (K - k0 > 0 ? K - k0 : 0);
+    TernaryBits tb{0u, 0u};
+    if (DTYPE == 0) {
+        const uint16_t *row = (const uint16_t *)A + (int64_t)m * lda;
+        uint16_t v[8];
+        if (nvalid == 8 && vec_ok) {
+            uint4 q = *(const uint4 *)(row + k0);
+            v[0] = q.x & 0xffff; v[1] = q.x >> 16; v[2] = q.y & 0xffff; v[3] = q.y >> 16;
+            v[4] = q.z & 0xffff; v[5] = q.z >> 16; v[6] = q.w & 0xffff; v[7] = q.w >> 16;
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = i < nvalid ? row[k0 + i] : (uint16_t)0;
+        }
+        float s = load_scale(s_a, m);
+        bool ok = (s > 0.0f) && (s < __builtin_inff());
+        tb = ternary_bits_fp16(v, nvalid, 0.5f * s, ok);
+    } else {
+        const int8_t *row = (const int8_t *)A + (int64_t)m * lda;
+        int8_t v[8];
+        if (nvalid == 8 && vec_ok) {
+            uint2 q = *(const uint2 *)(row + k0);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                v[i] = (int8_t)(q.x >> (8 * i));
+                v[4 + i] = (int8_t)(q.y >> (8 * i));
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = i < nvalid ? row[k0 + i] : (int8_t)0;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            tb.nz |= (uint32_t)(v[i] != 0) << i;
+            tb.neg |= (uint32_t)(v[i] < 0) << i;
+        }
+    }
+    const int lane = threadIdx.x & 63;
+    uint32_t wm = quad_word(tb.nz, lane);
+    uint32_t ws = quad_word(tb.neg, lane);
+    const int64_t widx = (int64_t)m * rw + (c >> 2);
+    if ((lane & 3) == 0) mask[widx] = wm;
+    if ((lane & 3) == 1) sign[widx] = ws;
+}
+
+template <int DTYPE>
+__global__ __launch_bounds__(kThreads) void k_pack_weights(const void *__restrict__ W, int64_t ldw,
+                                                           int N, int K, int rw,
+                                                           uint32_t *__restrict__ wsign, int vec_ok)
+{
+    const int c8 = rw * 4;
+    const int64_t total = (int64_t)N * c8;
+    const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (gid >= total) return;
+    const int n = (int)(gid / c8);
+    const int c = (int)(gid - (int64_t)n * c8);
+    const int k0 = c * 8;
+    const int nvalid = K - k0 >= 8 ? 8 : (K - k0 > 0 ? K - k0 : 0);
+    uint32_t bits = 0;
+    if (DTYPE == 0) {
+        const uint16_t *row = (const uint16_t *)W + (int64_t)n * ldw;
+        uint16_t v[8];
+        if (nvalid == 8 && vec_ok) {
+            uint4 q = *(const uint4 *)(row + k0);
+            v[0] = q.x & 0xffff; v[1] = q.x >> 16; v[2] = q.y & 0xffff; v[3] = q.y >> 16;
+            v[4] = q.z & 0xffff; v[5] = q.z >> 16; v[6] = q.w & 0xffff; v[7] = q.w >> 16;
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = i < nvalid ? row[k0 + i] : (uint16_t)0;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            float w = half_bits_to_float(v[i]);
+            bits |= (uint32_t)((i < nvalid) && !(w >= 0.0f)) << i;  // "otherwise" includes NaN
+        }
+    } else {
+        const int8_t *row = (const int8_t *)W + (int64_t)n * ldw;
+        if (nvalid == 8 && vec_ok) {
+            uint2 q = *(const uint2 *)(row + k0);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                bits |= ((q.x >> (8 * i + 7)) & 1u) << i;
+                bits |= ((q.y >> (8 * i + 7)) & 1u) << (4 + i);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                int8_t w = i < nvalid ? row[k0 + i] : (int8_t)0;
+                bits |= (uint32_t)(w < 0) << i;
+            }
+        }
+    }
+    const int lane = threadIdx.x & 63;
+    uint32_t word = quad_word(bits, lane);
+    if ((lane & 3) == 0) wsign[(int64_t)n * rw + (c >> 2)] = word;
+}
+
+// nnz[m] = popcount of mask row m; one wavefront per row.
+__global__ __launch_bounds__(kThreads) void k_row_popcount(const uint32_t *__restrict__ mask, int M,
+                                                           int rw, int32_t *__restrict__ nnz)
+{
+    const int lane = threadIdx.x & 63;
+    const int m = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (m >= M) return;
+    int c = 0;
+    for (int w = lane; w < rw; w += 64) c += __popc(mask[(int64_t)m * rw + w]);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) c += __shfl_xor(c, off);
+    if (lane == 0) nnz[m] = c;
+}
+
+}  // namespace
+
+hipError_t launch_quantize_pack(const void *A, int dtype, int64_t lda, ScaleArg s_a, int M, int K,
+                                uint32_t *mask, uint32_t *sign, int32_t *nnz, hipStream_t st)
+{
+    const int rw = 4 * ((K + 127) / 128);
+    const int64_t total = (int64_t)M * rw * 4;
+    if (total == 0) return hipSuccess;
+    const unsigned grid = (unsigned)((total + kThreads - 1) / kThreads);
+    const int elt = dtype == 0 ? 2 : 1;
+    const int vec_ok = (((uintptr_t)A % (8 * elt)) == 0 && (lda % 8) == 0) ? 1 : 0;
+    if (dtype == 0)
+        hipLaunchKernelGGL(k_quantize_pack<0>, dim3(grid), dim3(kThreads), 0, st, A, lda, s_a, M, K, rw,
+                           mask, sign, vec_ok);
+    else
+        hipLaunchKernelGGL(k_quantize_pack<1>, dim3(grid), dim3(kThreads), 0, st, A, lda, s_a, M, K, rw,
+                           mask, sign, vec_ok);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || nnz == nullptr) return e;
+    hipLaunchKernelGGL(k_row_popcount, dim3((M + 3) / 4), dim3(kThreads), 0, st, mask, M, rw, nnz);
+    return hipGetLastError();
+}
+
+hipError_t launch_pack_weights(const void *W, int dtype, int64_t ldw, int N, int K, uint32_t *wsign,
+                               hipStream_t st)
+{
+    const int rw = 4 * ((K + 127) / 128);
+    const int64_t total = (int64_t)N * rw * 4;
+    if (total == 0) return hipSuccess;
+    const unsigned grid = (unsigned)((total + kThreads - 1) / kThreads);
+    const int elt = dtype == 0 ? 2 : 1;
+    const int vec_ok = (((uintptr_t)W % (8 * elt)) == 0 && (ldw % 8) == 0) ? 1 : 0;
+    if (dtype == 0)
+        hipLaunchKernelGGL(k_pack_weights<0>, dim3(grid), dim3(kThreads), 0, st, W, ldw, N, K, rw, wsign,
+                           vec_ok);
+    else
+        hipLaunchKernelGGL(k_pack_weights<1>, dim3(grid), dim3(kThreads), 0, st, W, ldw, N, K, rw, wsign,
+                           vec_ok);
+    return hipGetLastError();
+}
+
+}  // namespace bwta

@@ -1,0 +1,95 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every function
+the header declares, and rejects bad arguments before anything could be enqueued."""
+import os
+import re
+
+import pytest
+
+from paper_2604_03957_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x7F0000001000  # a well-aligned, never dereferenced "device" address
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "bwta.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(bwta_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = declared_functions()
+    assert set(names) == set(B.EXPORTS)
+    for n in names:
+        assert hasattr(B.raw(), n), n
+
+
+def test_row_words_and_workspace():
+    assert [B.plane_row_words(k) for k in (0, 1, 128, 129, 768, 4096, 11008)] == [0, 4, 4, 8, 24, 128, 344]
+    assert B.workspace_bytes(0, 5, 5) == 0
+    ws = B.workspace_bytes(4096, 3072, 768)
+    assert ws % 256 == 0 and ws >= 2 * 4096 * 24 * 4
+    assert B.version() >= 1
+    assert B.strerror(B.ERR_ALIGN) and B.strerror(0) == "ok"
+
+
+def test_path_selection():
+    assert B.get_path() == B.PATH_AUTO
+    B.set_path(B.PATH_POPC)
+    assert B.get_path() == B.PATH_POPC
+    B.set_path(B.PATH_AUTO)
+    with pytest.raises(B.BwtaError) as e:
+        B.set_path(7)
+    assert e.value.code == B.ERR_UNSUPPORTED
+    assert B.auto_path(1, 11008, 4096) == B.PATH_POPC
+    assert B.auto_path(2048, 4096, 4096) == B.PATH_MFMA
+
+
+def _code(fn, *a, **k):
+    with pytest.raises(B.BwtaError) as e:
+        fn(*a, **k)
+    return e.value.code
+
+
+def test_quantize_pack_rejects_bad_arguments():
+    q = B.bwta_quantize_pack_act
+    kw = dict(M=4, K=256, stream=0, scale_mode=B.SCALE_VECTOR)
+    assert _code(q, None, FAKE, FAKE, FAKE, **kw) == B.ERR_NULL
+    assert _code(q, FAKE, None, FAKE, FAKE, **kw) == B.ERR_NULL          # scale needed in VECTOR mode
+    assert _code(q, FAKE, FAKE, FAKE + 4, FAKE, **kw) == B.ERR_ALIGN       # planes are 16-byte aligned
+    assert _code(q, FAKE, FAKE, FAKE, FAKE, **dict(kw, lda=255)) == B.ERR_SHAPE
+    assert _code(q, FAKE, FAKE, FAKE, FAKE, **dict(kw, M=-1)) == B.ERR_SHAPE
+    assert _code(q, FAKE, FAKE, FAKE, FAKE, **dict(kw, K=0)) == B.ERR_SHAPE
+    assert _code(q, FAKE, FAKE, FAKE, FAKE, **dict(kw, a_dtype=9)) == B.ERR_UNSUPPORTED
+    assert _code(q, FAKE, FAKE, FAKE, FAKE, **dict(kw, scale_mode=5)) == B.ERR_UNSUPPORTED
+    q(FAKE, FAKE, FAKE, FAKE, **dict(kw, M=0))                            # empty input is a no-op
+
+
+def test_pack_weights_rejects_bad_arguments():
+    p = B.bwta_pack_weights
+    assert _code(p, None, FAKE, N=4, K=128, stream=0) == B.ERR_NULL
+    assert _code(p, FAKE, FAKE + 8, N=4, K=128, stream=0) == B.ERR_ALIGN
+    assert _code(p, FAKE, FAKE, N=4, K=128, ldw=64, stream=0) == B.ERR_SHAPE
+    assert _code(p, FAKE, FAKE, N=4, K=128, w_dtype=3, stream=0) == B.ERR_UNSUPPORTED
+    p(FAKE, FAKE, N=0, K=128, stream=0)
+
+
+def test_gemm_and_linear_reject_bad_arguments():
+    g = B.bwta_gemm
+    ws = B.workspace_bytes(8, 8, 128)
+    kw = dict(M=8, N=8, K=128, stream=0, workspace_bytes=ws, a_scale_mode=B.SCALE_VECTOR,
+              w_scale_mode=B.SCALE_VECTOR)
+    assert _code(g, None, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, **kw) == B.ERR_NULL
+    assert _code(g, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, **kw) == B.ERR_NULL   # no output at all
+    assert _code(g, FAKE, FAKE, FAKE + 4, FAKE, FAKE, FAKE, FAKE, FAKE, **kw) == B.ERR_ALIGN
+    assert _code(g, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, **dict(kw, ldo=7)) == B.ERR_SHAPE
+    assert _code(g, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, **kw) == B.ERR_WORKSPACE
+    assert _code(g, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, **dict(kw, workspace_bytes=ws - 1)) == B.ERR_WORKSPACE
+    assert _code(g, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE + 16, **kw) == B.ERR_ALIGN
+    assert _code(g, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, **kw) == B.ERR_NULL    # s_a missing
+    g(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, **dict(kw, N=0))
+    lin = B.bwta_linear
+    assert _code(lin, FAKE, FAKE, FAKE, FAKE, None, FAKE, **kw) == B.ERR_NULL
+    assert _code(lin, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, **dict(kw, lda=100)) == B.ERR_SHAPE
+    assert _code(lin, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, **dict(kw, workspace_bytes=0)) == B.ERR_WORKSPACE
+    lin(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, **dict(kw, M=0))

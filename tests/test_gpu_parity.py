@@ -1,0 +1,219 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle, element by element.
+
+Bars: packed planes, nnz and int32 accumulators bit-exact; fp16 outputs within 1e-3
+relative (the kernels are built to round exactly once, so in practice they are bit-equal
+and the tests report that too).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import (dev, gpu_gemm, gpu_linear, gpu_pack_weights, gpu_quantize_pack, host_u32,
+                      max_rel_err, same_half)
+from paper_2604_03957_amd import binding as B
+from paper_2604_03957_amd import synth
+
+pytestmark = pytest.mark.gpu
+RTOL = 1e-3
+PATHS = [B.PATH_POPC, B.PATH_MFMA]
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+# ---- ternarise + pack ---------------------------------------------------------------------
+
+def _activation_case(seed, M, K, lda=None):
+    lda = K if lda is None else lda
+    A = (synth.gaussian(seed, 1, M * lda).reshape(M, lda) * 1.3).astype(np.float16)
+    s = synth.scales(seed, 2, M, 0.3, 2.5)
+    # plant exact ties and special values
+    for m in range(min(M, 6)):
+        h = np.float16(0.5 * float(s[m]))
+        vals = [h, -h, np.nextafter(h, np.float16(0)), np.nextafter(-h, np.float16(-np.inf)),
+                np.float16(np.nan), np.float16(np.inf), np.float16(-np.inf), np.float16(-0.0)]
+        for i, v in enumerate(vals):
+            if i < K:
+                A[m, (7 * m + 5 * i) % K] = v
+    return A, s
+
+
+@pytest.mark.parametrize("M,K,lda", [(5, 40, None), (64, 768, None), (33, 300, 304), (257, 1001, 1003),
+                                     (3, 4096, None), (2, 11008, None), (1, 1, None), (130, 129, 136)])
+def test_quantize_pack_fp16_matches_oracle(M, K, lda):
+    _say("quantize fp16", M, K, lda)
+    A, s = _activation_case(100 + M, M, K, lda)
+    t = oracle.ternarize(np.ascontiguousarray(A[:, :K]), s)
+    want = oracle.pack_act(t)
+    got = gpu_quantize_pack(A, s, K=K)
+    for w, g, name in zip(want, got, ("mask", "sign", "nnz")):
+        assert np.array_equal(w, g), name
+
+
+def test_quantize_pack_scale_modes_and_bad_scales():
+    M, K = 9, 200
+    A, _ = _activation_case(7, M, K)
+    one = oracle.pack_act(oracle.ternarize(A, None))
+    got = gpu_quantize_pack(A, None)
+    assert all(np.array_equal(w, g) for w, g in zip(one, got))
+    sc = np.array([0.75], np.float16)
+    want = oracle.pack_act(oracle.ternarize(A, sc))
+    got = gpu_quantize_pack(A, sc)
+    assert all(np.array_equal(w, g) for w, g in zip(want, got))
+    bad = np.array([1.0, 0.0, -1.0, np.inf, np.nan, 2.0 ** -24, 6e-5, 65504.0, 1.5], np.float16)
+    want = oracle.pack_act(oracle.ternarize(A, bad))
+    got = gpu_quantize_pack(A, bad)
+    assert all(np.array_equal(w, g) for w, g in zip(want, got))
+    assert not got[0][1:5].any()          # rows with an invalid scale are all zero
+
+
+def test_quantize_pack_every_half_pattern():
+    A = np.arange(65536, dtype=np.uint32).astype(np.uint16).view(np.float16).reshape(16, 4096)
+    for sv in (1.0, 0.37, 2.0 ** -14, 2.0 ** -24, 900.0):
+        s = np.full(16, sv, np.float16)
+        want = oracle.pack_act(oracle.ternarize(A, s))
+        got = gpu_quantize_pack(A, s)
+        assert all(np.array_equal(w, g) for w, g in zip(want, got)), sv
+
+
+@pytest.mark.parametrize("M,K,lda", [(64, 768, None), (7, 333, 335), (2, 11008, None)])
+def test_quantize_pack_int8_matches_oracle(M, K, lda):
+    lda = K if lda is None else lda
+    t = synth.ternary(5, M, (M, lda), 0.4)
+    want = oracle.pack_act(np.ascontiguousarray(t[:, :K]))
+    got = gpu_quantize_pack(t, None, K=K)
+    assert all(np.array_equal(w, g) for w, g in zip(want, got))
+
+
+def test_quantize_pack_unaligned_base_pointer():
+    M, K = 6, 264
+    A, s = _activation_case(3, M, K + 8)
+    flat = dev(A.reshape(-1))
+    view = flat[1:]                                   # 2-byte aligned only
+    ref = A.reshape(-1)[1:1 + (M - 1) * (K + 8) + K]
+    rows = np.stack([ref[m * (K + 8): m * (K + 8) + K] for m in range(M)])
+    want = oracle.pack_act(oracle.ternarize(rows, s))
+    rw = B.plane_row_words(K)
+    mask = torch.zeros((M, rw), dtype=torch.int32, device="cuda:0")
+    sign = torch.zeros_like(mask)
+    B.bwta_quantize_pack_act(view, dev(s), mask, sign, None, M=M, K=K, lda=K + 8)
+    torch.cuda.synchronize()
+    assert np.array_equal(host_u32(mask), want[0]) and np.array_equal(host_u32(sign), want[1])
+
+
+@pytest.mark.parametrize("N,K", [(5, 40), (768, 768), (17, 1001), (3, 11008)])
+def test_pack_weights_matches_oracle(N, K):
+    w = synth.binary_pm1(11, N, (N, K))
+    want = oracle.pack_weights(w)
+    assert np.array_equal(host_u32(gpu_pack_weights(w)), want)
+    Wf = (synth.gaussian(12, N, N * K).reshape(N, K)).astype(np.float16)
+    Wf[0, :4] = np.array([0.0, -0.0, np.nan, -1e-7], np.float16)
+    want = oracle.pack_weights(oracle.sign_weights(Wf))
+    assert np.array_equal(host_u32(gpu_pack_weights(Wf)), want)
+
+
+# ---- product + epilogue ---------------------------------------------------------------------
+
+def _gemm_case(seed, M, N, K, p0=0.45):
+    t = synth.ternary(seed, 1, (M, K), p0)
+    w = synth.binary_pm1(seed, 2, (N, K))
+    return t, w, synth.scales(seed, 3, M), synth.scales(seed, 4, N)
+
+
+def _check_gemm(t, w, s_a, s_w, path, dirty_sign=False):
+    M, K = t.shape
+    N = w.shape[0]
+    mask, sign, _ = oracle.pack_act(t)
+    ws = oracle.pack_weights(w)
+    want_acc = oracle.gemm_unpacked(t, w)
+    want_out = oracle.epilogue(want_acc, s_a, s_w)
+    if dirty_sign:
+        sign = sign | (~mask & np.uint32(0x5A5A5A5A))
+    acc, out = gpu_gemm(mask, sign, ws, s_a, s_w, M, N, K, path=path)
+    assert np.array_equal(acc, want_acc), "int32 accumulators differ"
+    err = max_rel_err(out, want_out)
+    assert err <= RTOL, err
+    return same_half(out, want_out)
+
+
+GEMM_SHAPES = [(64, 768, 768), (1, 64, 128), (3, 5, 33), (16, 100, 4096), (130, 200, 1000),
+               (300, 260, 2048), (257, 513, 1408), (70, 129, 11008), (4, 300, 11008)]
+
+
+@pytest.mark.parametrize("path", PATHS)
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+def test_gemm_matches_oracle(M, N, K, path):
+    _say("gemm", M, N, K, "path", path)
+    t, w, s_a, s_w = _gemm_case(1000 + M + N, M, N, K)
+    exact = _check_gemm(t, w, s_a, s_w, path)
+    assert exact, "fp16 outputs are within tolerance but not bit-equal"
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_gemm_config1_tiny(path):
+    c = synth.config1()
+    assert _check_gemm(c["t"], c["w"], c["s_a"], c["s_w"], path)
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_gemm_degenerate_inputs(path):
+    M, N, K = 40, 70, 600
+    t, w, s_a, s_w = _gemm_case(77, M, N, K)
+    _check_gemm(np.zeros_like(t), w, s_a, s_w, path)              # all-zero activation -> all-zero output
+    _check_gemm(np.ones_like(t), np.ones_like(w), s_a, s_w, path)   # every product +1 -> K
+    _check_gemm(-np.ones_like(t), np.ones_like(w), s_a, s_w, path)  # -> -K
+    _check_gemm(t, w, s_a, s_w, path, dirty_sign=True)            # sign bits under a zero mask are ignored
+    big = s_a.copy(); big[:] = np.float16(60000.0)                # overflow to +-Inf in the epilogue
+    _check_gemm(t, w, big, s_w, path)
+    tiny = s_w.copy(); tiny[:] = np.float16(2.0 ** -24)           # subnormal fp16 results
+    _check_gemm(t, w, np.full(M, 2.0 ** -10, np.float16), tiny, path)
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_gemm_output_selection_and_scale_modes(path):
+    M, N, K = 20, 36, 256
+    t, w, s_a, s_w = _gemm_case(5, M, N, K)
+    mask, sign, _ = oracle.pack_act(t)
+    ws = oracle.pack_weights(w)
+    want_acc = oracle.gemm_unpacked(t, w)
+    acc, out = gpu_gemm(mask, sign, ws, None, None, M, N, K, path=path)
+    assert np.array_equal(acc, want_acc) and same_half(out, oracle.epilogue(want_acc, None, None))
+    acc, _ = gpu_gemm(mask, sign, ws, s_a, s_w, M, N, K, path=path, want_out=False)
+    assert np.array_equal(acc, want_acc)
+    _, out = gpu_gemm(mask, sign, ws, s_a[:1], s_w[:1], M, N, K, path=path, want_acc=False)
+    assert same_half(out, oracle.epilogue(want_acc, s_a[:1], s_w[:1]))
+
+
+def test_empty_problem_is_a_noop():
+    ws = torch.empty(256, dtype=torch.uint8, device="cuda:0")
+    z = torch.empty(0, dtype=torch.int32, device="cuda:0")
+    B.bwta_gemm(z, z, z, None, None, z, None, ws, M=0, N=8, K=128)
+    B.bwta_quantize_pack_act(z, None, z, z, None, M=0, K=128)
+    torch.cuda.synchronize()
+
+
+# ---- the whole layer ----------------------------------------------------------------------
+
+@pytest.mark.parametrize("path", PATHS)
+@pytest.mark.parametrize("which", ["up", "down"])
+def test_linear_ffn_reduced_m(which, path):
+    c = synth.config2(which, M=200)
+    _say("linear", c["name"], "path", path)
+    _, _, want = oracle.linear(c["A"], c["s_a"], c["w"], c["s_w"])
+    wsign = gpu_pack_weights(c["w"])
+    out = gpu_linear(c["A"], c["s_a"], wsign, c["s_w"], c["N"], path=path)
+    assert max_rel_err(out, want) <= RTOL
+    assert same_half(out, want)
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_linear_laplace_block_input(path):
+    x = synth.laplace_activations(4, 1, 96, 4096)
+    s = synth.token_scales_l1(x)
+    w = synth.binary_pm1(4, 10, (160, 4096))
+    s_w = synth.scales(4, 11, 160)
+    _, _, want = oracle.linear(x, s, w, s_w)
+    out = gpu_linear(x, s, gpu_pack_weights(w), s_w, 160, path=path)
+    assert same_half(out, want)
