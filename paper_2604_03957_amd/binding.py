@@ -7,6 +7,10 @@ Importing this module without the compiled library raises -- there is no fallbac
 import ctypes
 import os
 
+# torch ships its own HIP runtime; load it first so that libbwta.so binds to the same runtime
+# (same SONAME) instead of bringing a second one into the process.
+import torch  # noqa: F401
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "csrc", "libbwta.so")
 
@@ -85,7 +89,6 @@ def _ptr(x):
 def _stream(stream):
     if stream is not None:
         return stream if isinstance(stream, int) else stream.cuda_stream
-    import torch
     return torch.cuda.current_stream().cuda_stream
 
 
