@@ -1,0 +1,270 @@
+#!/usr/bin/env python3
+"""Benchmark of the BWTA linear hot path on one MI355X.
+
+Default workload ("c2_ffn"): the encoder-layer FFN configuration -- fp16 activations
+[4096, 768] -> 3072 and [4096, 3072] -> 768, each through the whole path (ternarise + pack +
+integer product + scale epilogue, i.e. one bwta_linear call per layer).  One step = both
+layers.  Inputs are resident in HBM before the timed region; weights are packed beforehand
+(the paper packs weights before inference).
+
+Prints ONE JSON line.  `value` is effective TOPS = 2*M*N*K summed over the step / time
+(zeros counted, dense-equivalent work).  `roofline` is for the dominant kernel, timed live
+with HIP events on the launch stream; `cpu_baseline` is the CPU oracle timed on the host
+cores of the same box.  Other workloads: --workload c1_tiny | c3_prefill | c4_decode.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5000.0   # MI355X dense int8 MFMA, TOP/s
+PEAK_HBM_GBS = 8000.0     # MI355X HBM3E, GB/s
+PEAK_VALU_POPC_TOPS = 1258.0  # 256 CU * 64 lanes * 2.4 GHz * 32 MAC per 2 VALU ops * 2 ops/MAC
+
+
+def _dev(a, torch):
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint32:
+        a = a.view(np.int32)
+    return torch.from_numpy(a).to("cuda:0")
+
+
+def _event_ms(torch, fn, reps, warmup):
+    """Average duration of fn() in ms, HIP events on the current (launch) stream."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+class Layer:
+    """One linear layer's device buffers."""
+
+    def __init__(self, cfg, torch, B, from_fp16):
+        self.M, self.N, self.K = cfg["M"], cfg["N"], cfg["K"]
+        M, N, K = self.M, self.N, self.K
+        self.rw = B.plane_row_words(K)
+        self.s_a = _dev(cfg["s_a"], torch)
+        self.s_w = _dev(cfg["s_w"], torch)
+        w = _dev(cfg["w"], torch)
+        self.wsign = torch.empty((N, self.rw), dtype=torch.int32, device="cuda:0")
+        B.bwta_pack_weights(w, self.wsign, N=N, K=K)
+        del w
+        self.out = torch.empty((M, N), dtype=torch.float16, device="cuda:0")
+        self.ws = torch.empty(max(B.workspace_bytes(M, N, K), 256), dtype=torch.uint8, device="cuda:0")
+        self.mask = torch.empty((M, self.rw), dtype=torch.int32, device="cuda:0")
+        self.sign = torch.empty_like(self.mask)
+        if from_fp16:
+            self.A = _dev(cfg["A"], torch)
+            B.bwta_quantize_pack_act(self.A, self.s_a, self.mask, self.sign, None, M=M, K=K)
+        else:
+            self.A = _dev(cfg["t"], torch)
+            B.bwta_quantize_pack_act(self.A, None, self.mask, self.sign, None, M=M, K=K, a_dtype=B.DTYPE_INT8)
+        torch.cuda.synchronize()
+        self.ops = 2.0 * M * N * K
+
+    def linear(self, B):
+        B.bwta_linear(self.A, self.s_a, self.wsign, self.s_w, self.out, self.ws, M=self.M, N=self.N, K=self.K)
+
+    def quantize(self, B):
+        B.bwta_quantize_pack_act(self.A, self.s_a, self.mask, self.sign, None, M=self.M, K=self.K)
+
+    def gemm(self, B):
+        B.bwta_gemm(self.mask, self.sign, self.wsign, self.s_a, self.s_w, None, self.out, self.ws,
+                    M=self.M, N=self.N, K=self.K)
+
+    def gemm_bytes(self):
+        M, N, K = self.M, self.N, self.K
+        return N * self.rw * 4 + 2 * M * self.rw * 4 + 2 * (M + N) + 2 * M * N
+
+    def quantize_bytes(self):
+        return self.M * self.K * 2 + 2 * self.M * self.rw * 4 + 2 * self.M
+
+
+def cpu_baseline_c2(cfgs, target_s=12.0):
+    """The oracle, as it stands, on the same workload: whole layers, repeated to ~target_s."""
+    import oracle
+    threads = oracle.num_threads()
+    ops_per_pass = sum(2.0 * c["M"] * c["N"] * c["K"] for c in cfgs)
+    t0 = time.perf_counter()
+    passes = 0
+    while True:
+        for c in cfgs:
+            oracle.linear(c["A"], c["s_a"], c["w"], c["s_w"])
+        passes += 1
+        dt = time.perf_counter() - t0
+        if dt >= target_s or passes >= 50:
+            break
+    return {"value": round(ops_per_pass * passes / dt / 1e12, 5), "unit": "TOPS", "cores": threads,
+            "kind": "oracle", "sample": "%d full passes of the same two layers (all %d tokens), %.1f s"
+            % (passes, cfgs[0]["M"], dt)}
+
+
+def run_c2(args, torch, B, synth):
+    cfgs = [synth.config2("up"), synth.config2("down")]
+    layers = [Layer(c, torch, B, from_fp16=True) for c in cfgs]
+
+    def step():
+        for L in layers:
+            L.linear(B)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / args.steps
+    ops = sum(L.ops for L in layers)
+    value = ops / (ms_per_step * 1e-3) / 1e12
+
+    # per-kernel durations, HIP events on the launch stream
+    kern = []
+    for L, c in zip(layers, cfgs):
+        tq = _event_ms(torch, lambda: L.quantize(B), args.steps, args.warmup)
+        tg = _event_ms(torch, lambda: L.gemm(B), args.steps, args.warmup)
+        kern.append({"layer": c["name"], "quantize_us": round(tq * 1e3, 2), "gemm_us": round(tg * 1e3, 2),
+                     "quantize_GBs": round(L.quantize_bytes() / (tq * 1e-3) / 1e9, 1),
+                     "gemm_TOPS": round(L.ops / (tg * 1e-3) / 1e12, 2),
+                     "path": {B.PATH_MFMA: "mfma_int8", B.PATH_FP4: "mfma_fp4", B.PATH_POPC: "popc"}[B.auto_path(L.M, L.N, L.K)]})
+    gemm_ms = [k["gemm_us"] / 1e3 for k in kern]
+    avg_gemm_ms = sum(gemm_ms) / len(gemm_ms)
+    achieved = (ops / len(layers)) / (avg_gemm_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "k_gemm_mfma (int8 MFMA product + epilogue), mean of the two layers",
+                "achieved": round(achieved, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
+                "frac": round(achieved / PEAK_INT8_TOPS, 4), "traffic": None}
+    out = {"metric": "BWTA linear effective TOPS (ternarize+pack+GEMM+epilogue), encoder FFN shapes",
+           "value": round(value, 3), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+           "config": {"workload": "c2_ffn: M=4096 (32x128 tokens), K=768->N=3072 and K=3072->N=768, fp16 in/out",
+                      "path": "full (bwta_linear x2 per step)"},
+           "roofline": roofline, "kernels": kern}
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline_c2(cfgs)
+    return out
+
+
+def run_c3(args, torch, B, synth):
+    res = []
+    tot_ops = tot_ms = 0.0
+    for which in ("qkvo", "upgate", "down"):
+        c = synth.config3(which)
+        L = Layer(c, torch, B, from_fp16=False)
+        per = {}
+        for name, path in (("fp4", B.PATH_FP4), ("mfma", B.PATH_MFMA), ("popc", B.PATH_POPC)):
+            B.set_path(path)
+            ms = _event_ms(torch, lambda: L.gemm(B), args.steps, args.warmup)
+            per[name + "_us"] = round(ms * 1e3, 1)
+            per[name + "_TOPS"] = round(L.ops / (ms * 1e-3) / 1e12, 1)
+        B.set_path(B.PATH_AUTO)
+        ms = _event_ms(torch, lambda: L.gemm(B), args.steps, args.warmup)
+        tot_ops += L.ops
+        tot_ms += ms
+        res.append(dict(layer=c["name"], M=L.M, N=L.N, K=L.K, auto_us=round(ms * 1e3, 1),
+                        auto_TOPS=round(L.ops / (ms * 1e-3) / 1e12, 1), **per))
+        del L
+    value = tot_ops / (tot_ms * 1e-3) / 1e12
+    return {"metric": "BWTA GEMM effective TOPS (prefill linears from packed planes)", "value": round(value, 2),
+            "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": round(tot_ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "int8", "data": "synthetic",
+            "config": {"workload": "c3_prefill: M=2048, (K,N) in {(4096,4096),(4096,11008),(11008,4096)}"},
+            "roofline": {"bound": "mfma", "achieved": round(value, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
+                         "frac": round(value / PEAK_INT8_TOPS, 4), "traffic": None},
+            "kernels": res}
+
+
+def run_c4(args, torch, B, synth):
+    """Decode: stream L distinct packed weight matrices (> Infinity Cache) per timed region."""
+    nmat = args.decode_matrices
+    res = []
+    best = None
+    for which in ("upgate", "down"):
+        for M in (1, 4, 16):
+            c = synth.config4(which, M)
+            L = Layer(c, torch, B, from_fp16=False)
+            # L distinct weight matrices: rotate the packed rows so the bits differ
+            mats = [torch.roll(L.wsign, shifts=i, dims=0).contiguous() for i in range(nmat)]
+
+            def chain():
+                for w in mats:
+                    B.bwta_gemm(L.mask, L.sign, w, L.s_a, L.s_w, None, L.out, L.ws, M=L.M, N=L.N, K=L.K)
+
+            ms = _event_ms(torch, chain, max(2, args.steps // 4), 1) / nmat
+            gbs = L.gemm_bytes() / (ms * 1e-3) / 1e9
+            r = dict(layer=c["name"], M=M, N=L.N, K=L.K, us_per_matrix=round(ms * 1e3, 2), GBs=round(gbs, 1),
+                     frac_hbm=round(gbs / PEAK_HBM_GBS, 4))
+            res.append(r)
+            if best is None or gbs > best:
+                best = gbs
+            del mats, L
+    mean = float(np.mean([r["GBs"] for r in res]))
+    return {"metric": "BWTA decode GEMM achieved HBM GB/s (weights streamed once)", "value": round(mean, 1),
+            "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": round(float(np.mean([r["us_per_matrix"] for r in res])) / 1e3, 6),
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
+            "config": {"workload": "c4_decode: M in {1,4,16}, (K,N) in {(4096,11008),(11008,4096)}, %d distinct weight matrices chained" % nmat},
+            "roofline": {"bound": "hbm", "achieved": round(mean, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                         "frac": round(mean / PEAK_HBM_GBS, 4), "traffic": None},
+            "kernels": res}
+
+
+def run_c1(args, torch, B, synth):
+    c = synth.config1()
+    L = Layer(c, torch, B, from_fp16=False)
+    res = {}
+    for name, path in (("mfma", B.PATH_MFMA), ("popc", B.PATH_POPC)):
+        B.set_path(path)
+        res[name + "_us"] = round(_event_ms(torch, lambda: L.gemm(B), args.steps, args.warmup) * 1e3, 2)
+    B.set_path(B.PATH_AUTO)
+    ms = _event_ms(torch, lambda: L.gemm(B), args.steps, args.warmup)
+    return {"metric": "BWTA tiny GEMM latency", "value": round(ms * 1e3, 2), "unit": "us", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 6), "higher_is_better": False,
+            "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+            "config": {"workload": "c1_tiny: M=64, N=768, K=768"}, "kernels": res}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c2_ffn", choices=["c2_ffn", "c1_tiny", "c3_prefill", "c4_decode"])
+    ap.add_argument("--decode-matrices", type=int, default=64)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the BWTA hot path is a single-GPU kernel "
+              "path; sharding is described in DESIGN.md). Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
+        sys.exit(3)
+    from paper_2604_03957_amd import binding as B
+    from paper_2604_03957_amd import synth
+    torch.cuda.set_device(0)
+    run = {"c2_ffn": run_c2, "c1_tiny": run_c1, "c3_prefill": run_c3, "c4_decode": run_c4}[args.workload]
+    out = run(args, torch, B, synth)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

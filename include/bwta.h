@@ -57,9 +57,10 @@ enum {
 enum { BWTA_DTYPE_FP16 = 0, BWTA_DTYPE_INT8 = 1 };
 enum { BWTA_SCALE_NONE = 0, BWTA_SCALE_SCALAR = 1, BWTA_SCALE_VECTOR = 2 };
 /* Which contraction kernel bwta_gemm / bwta_linear use.  AUTO picks per shape regime from
- * measurements on MI355X; the other two force the wave64 popcount kernels or the int8
- * matrix-core (MFMA) kernel.  All three produce identical bits. */
-enum { BWTA_PATH_AUTO = 0, BWTA_PATH_POPC = 1, BWTA_PATH_MFMA = 2 };
+ * measurements on MI355X; the others force the wave64 popcount kernels, the int8 matrix-core
+ * (MFMA) kernel that widens bit planes to int8, or the FP4 matrix-core kernel (+-1 and 0 are
+ * exact in E2M1).  All of them produce identical bits. */
+enum { BWTA_PATH_AUTO = 0, BWTA_PATH_POPC = 1, BWTA_PATH_MFMA = 2, BWTA_PATH_FP4 = 3 };
 
 /* Words per packed row: 4 * ceil(K / 128).  Returns 0 for K <= 0. */
 int64_t bwta_plane_row_words(int K);
@@ -128,7 +129,7 @@ int bwta_last_hip_error(void);
 /* Select the contraction kernel family (process-wide).  Returns BWTA_OK or UNSUPPORTED. */
 int bwta_set_path(int path);
 int bwta_get_path(void);
-/* Which family AUTO resolves to for a shape: BWTA_PATH_POPC or BWTA_PATH_MFMA. */
+/* Which family AUTO resolves to for a shape: BWTA_PATH_POPC, BWTA_PATH_MFMA or BWTA_PATH_FP4. */
 int bwta_auto_path(int M, int N, int K);
 /* Library version, major * 100 + minor. */
 int bwta_version(void);

@@ -18,7 +18,7 @@ OK = 0
 ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = -1, -2, -3, -4, -5, -6
 DTYPE_FP16, DTYPE_INT8 = 0, 1
 SCALE_NONE, SCALE_SCALAR, SCALE_VECTOR = 0, 1, 2
-PATH_AUTO, PATH_POPC, PATH_MFMA = 0, 1, 2
+PATH_AUTO, PATH_POPC, PATH_MFMA, PATH_FP4 = 0, 1, 2, 3
 
 EXPORTS = ["bwta_plane_row_words", "bwta_workspace_bytes", "bwta_quantize_pack_act",
            "bwta_pack_weights", "bwta_gemm", "bwta_linear", "bwta_strerror", "bwta_last_hip_error",

@@ -31,10 +31,16 @@ int resolve_path(int M, int N, int K)
     return p == BWTA_PATH_AUTO ? bwta_auto_path(M, N, K) : p;
 }
 
-int run_gemm(const bwta::GemmArgs &g, hipStream_t st)
+// workspace layout: [mask planes | sign planes | FP4 activation fragments]
+int run_gemm(const bwta::GemmArgs &g, void *workspace, hipStream_t st)
 {
     int path = resolve_path(g.M, g.N, g.K);
+    if (path == BWTA_PATH_FP4) {
+        uint32_t *frag = (uint32_t *)((char *)workspace + 2 * plane_bytes(g.M, g.K));
+        return hip_result(bwta::launch_gemm_fp4(g, frag, st));
+    }
     if (path == BWTA_PATH_MFMA && bwta::gemm_mfma_supported(g)) return hip_result(bwta::launch_gemm_mfma(g, st));
+    if (bwta::gemv_popc_supported(g)) return hip_result(bwta::launch_gemv_popc(g, st));
     return hip_result(bwta::launch_gemm_popc(g, st));
 }
 
@@ -47,7 +53,8 @@ int64_t bwta_plane_row_words(int K) { return K <= 0 ? 0 : 4 * (((int64_t)K + 127
 size_t bwta_workspace_bytes(int M, int N, int K)
 {
     if (M <= 0 || N <= 0 || K <= 0) return 0;
-    return 2 * plane_bytes(M, K);  // mask + sign planes of bwta_linear
+    // mask + sign planes of bwta_linear, then the FP4 activation fragments of the FP4 kernel
+    return 2 * plane_bytes(M, K) + round_up(bwta::gemm_fp4_frag_bytes(M, K), 256);
 }
 
 int bwta_quantize_pack_act(const void *A, int a_dtype, int64_t lda, const void *s_a, int scale_mode,
@@ -112,7 +119,7 @@ int bwta_gemm(const uint32_t *mask, const uint32_t *sign, const uint32_t *wsign,
                      {(const uint16_t *)s_a, s_a ? a_scale_mode : BWTA_SCALE_NONE},
                      {(const uint16_t *)s_w, s_w ? w_scale_mode : BWTA_SCALE_NONE},
                      acc, (uint16_t *)out, ldo};
-    return run_gemm(g, (hipStream_t)stream);
+    return run_gemm(g, workspace, (hipStream_t)stream);
 }
 
 int bwta_linear(const void *A, int64_t lda, const void *s_a, int a_scale_mode, const uint32_t *wsign,
@@ -136,7 +143,7 @@ int bwta_linear(const void *A, int64_t lda, const void *s_a, int a_scale_mode, c
     bwta::GemmArgs g{mask, sign, wsign, M, N, K, (int)bwta_plane_row_words(K), sa,
                      {(const uint16_t *)s_w, s_w ? w_scale_mode : BWTA_SCALE_NONE},
                      nullptr, (uint16_t *)out, ldo};
-    return run_gemm(g, st);
+    return run_gemm(g, workspace, st);
 }
 
 const char *bwta_strerror(int code)
@@ -157,7 +164,7 @@ int bwta_last_hip_error(void) { return t_last_hip_error; }
 
 int bwta_set_path(int path)
 {
-    if (path != BWTA_PATH_AUTO && path != BWTA_PATH_POPC && path != BWTA_PATH_MFMA) return BWTA_ERR_UNSUPPORTED;
+    if (path < BWTA_PATH_AUTO || path > BWTA_PATH_FP4) return BWTA_ERR_UNSUPPORTED;
     g_path.store(path, std::memory_order_relaxed);
     return BWTA_OK;
 }
@@ -168,7 +175,7 @@ int bwta_auto_path(int M, int N, int K)
 {
     (void)N;
     (void)K;
-    return M >= 16 ? BWTA_PATH_MFMA : BWTA_PATH_POPC;
+    return M > 8 ? BWTA_PATH_FP4 : BWTA_PATH_POPC;
 }
 
 int bwta_version(void) { return 1; }

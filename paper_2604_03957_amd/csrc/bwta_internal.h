@@ -26,8 +26,13 @@ hipError_t launch_quantize_pack(const void *A, int dtype, int64_t lda, ScaleArg 
 hipError_t launch_pack_weights(const void *W, int dtype, int64_t ldw, int N, int K, uint32_t *wsign,
                                hipStream_t st);
 hipError_t launch_gemm_popc(const GemmArgs &g, hipStream_t st);
+bool gemv_popc_supported(const GemmArgs &g);
+hipError_t launch_gemv_popc(const GemmArgs &g, hipStream_t st);
 bool gemm_mfma_supported(const GemmArgs &g);
 hipError_t launch_gemm_mfma(const GemmArgs &g, hipStream_t st);
+
+size_t gemm_fp4_frag_bytes(int M, int K);
+hipError_t launch_gemm_fp4(const GemmArgs &g, uint32_t *frag, hipStream_t st);
 
 // ---- device helpers -------------------------------------------------------------------------
 
@@ -61,6 +66,77 @@ __device__ __forceinline__ uint16_t scaled_to_half(int acc, float s)
     uint16_t bits;
     __builtin_memcpy(&bits, &r, 2);
     return bits;
+}
+
+// Epilogue shared by the matrix-core kernels.  A wavefront owns WM x WN blocks of 32 x 32
+// accumulators in the MFMA layout (lane = column r32 of a block, register v = row
+// 8*(v/4) + 4*h + v%4).  Scaled fp16 results go through a wavefront-private LDS strip of 32 rows
+// so that global stores are 16 bytes per lane along rows; int32 accumulators (optional output,
+// used by tests) are stored directly.
+//   get(i, j, v)  -> exact int32 accumulator
+//   strip         -> this wavefront's LDS scratch, 32 * (32*WN + 8) halfs
+//   sa_lds        -> float s_a of the block's rows (index = row within block), filled by caller
+template <int WM, int WN, typename Get>
+__device__ __forceinline__ void store_wave_tile(const GemmArgs &g, int m_wave, int n_wave, int row_in_block0,
+                                                uint16_t *strip, const float *sa_lds, Get get)
+{
+    constexpr int PITCH = 32 * WN + 8;  // halfs
+    const int lane = threadIdx.x & 63, r32 = lane & 31, h = lane >> 5;
+    if (g.acc) {
+#pragma unroll
+        for (int j = 0; j < WN; ++j) {
+            const int n = n_wave + 32 * j + r32;
+#pragma unroll
+            for (int i = 0; i < WM; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = m_wave + 32 * i + 8 * (v >> 2) + 4 * h + (v & 3);
+                    if (m < g.M && n < g.N) g.acc[(int64_t)m * g.N + n] = get(i, j, v);
+                }
+        }
+    }
+    if (!g.out) return;
+    float sw[WN];
+#pragma unroll
+    for (int j = 0; j < WN; ++j) {
+        const int n = n_wave + 32 * j + r32;
+        sw[j] = n < g.N ? load_scale(g.s_w, n) : 0.0f;
+    }
+    const bool vec_ok = ((g.ldo & 7) == 0) && (((uintptr_t)g.out & 15) == 0);
+    constexpr int LPR = 4 * WN;        // lanes per row when each lane moves 8 halfs
+    constexpr int RPI = 64 / LPR;      // rows per store instruction
+#pragma unroll
+    for (int i = 0; i < WM; ++i) {
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = 8 * (v >> 2) + 4 * h + (v & 3);
+                const float sa = sa_lds[row_in_block0 + 32 * i + row];
+                strip[row * PITCH + 32 * j + r32] = scaled_to_half(get(i, j, v), sa * sw[j]);
+            }
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+        for (int rr = 0; rr < 32; rr += RPI) {
+            const int row = rr + lane / LPR, c8 = 8 * (lane % LPR);
+            const int m = m_wave + 32 * i + row, n = n_wave + c8;
+            if (m < g.M && n < g.N) {
+                const uint4 q = *(const uint4 *)(strip + row * PITCH + c8);
+                uint16_t *dst = g.out + (int64_t)m * g.ldo + n;
+                if (vec_ok && n + 8 <= g.N) {
+                    *(uint4 *)dst = q;
+                } else {
+                    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (n + e < g.N) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+                }
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    }
 }
 
 }  // namespace bwta

@@ -214,27 +214,19 @@ __global__ __launch_bounds__(256, 1) void k_gemm_mfma(GemmArgs g)
     }
     __syncthreads();
 
-    // epilogue: lane holds column n = r32 of each 32 x 32 block, rows 8*(v/4) + 4*h + v%4
+    // epilogue; the tile buffers are dead (last loop barrier), sT / sB live behind them
+    float *sa_lds = (float *)smem;
+    uint16_t *strip = (uint16_t *)(smem + T::BM) + wave * (32 * (32 * WN + 8));
+    for (int t = tid; t < T::BM; t += 256) sa_lds[t] = (m0 + t < g.M) ? load_scale(g.s_a, m0 + t) : 0.0f;
+    __syncthreads();
+    int b2[WN];
 #pragma unroll
-    for (int j = 0; j < WN; ++j) {
-        const int nl = wn * 32 * WN + 32 * j + r32;
-        const int n = n0 + nl;
-        if (n >= g.N) continue;
-        const int b2 = 2 * sB[nl];
-        const float sw = load_scale(g.s_w, n);
-#pragma unroll
-        for (int i = 0; i < WM; ++i) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int ml = wm * 32 * WM + 32 * i + 8 * (v >> 2) + 4 * h + (v & 3);
-                const int m = m0 + ml;
-                if (m >= g.M) continue;
-                const int a = sT[ml] + b2 - (acc[i][j][v] >> 4);
-                if (g.acc) g.acc[(int64_t)m * g.N + n] = a;
-                if (g.out) g.out[(int64_t)m * g.ldo + n] = scaled_to_half(a, load_scale(g.s_a, m) * sw);
-            }
-        }
-    }
+    for (int j = 0; j < WN; ++j) b2[j] = 2 * sB[wn * 32 * WN + 32 * j + r32];
+    store_wave_tile<WM, WN>(g, m0 + wm * WM * 32, n0 + wn * WN * 32, wm * WM * 32, strip, sa_lds,
+                            [&](int i, int j, int v) {
+                                const int ml = wm * 32 * WM + 32 * i + 8 * (v >> 2) + 4 * h + (v & 3);
+                                return sT[ml] + b2[j] - (acc[i][j][v] >> 4);
+                            });
 }
 
 template <int WM, int WN>

@@ -16,7 +16,7 @@ from paper_2604_03957_amd import synth
 
 pytestmark = pytest.mark.gpu
 RTOL = 1e-3
-PATHS = [B.PATH_POPC, B.PATH_MFMA]
+PATHS = [B.PATH_POPC, B.PATH_MFMA, B.PATH_FP4]
 
 
 def _say(*a):
@@ -149,6 +149,19 @@ def test_gemm_matches_oracle(M, N, K, path):
     t, w, s_a, s_w = _gemm_case(1000 + M + N, M, N, K)
     exact = _check_gemm(t, w, s_a, s_w, path)
     assert exact, "fp16 outputs are within tolerance but not bit-equal"
+
+
+DECODE_SHAPES = [(1, 7, 33), (2, 130, 128), (3, 257, 1000), (1, 1001, 4096), (4, 999, 4096), (8, 300, 4096),
+                 (5, 258, 8192), (1, 515, 11008), (4, 130, 11008), (8, 67, 11008), (2, 70, 16384),
+                 (3, 40, 16512)]
+
+
+@pytest.mark.parametrize("M,N,K", DECODE_SHAPES)
+def test_decode_shaped_gemm_matches_oracle(M, N, K):
+    _say("decode gemm", M, N, K)
+    t, w, s_a, s_w = _gemm_case(2000 + M + N, M, N, K, p0=0.5)
+    assert _check_gemm(t, w, s_a, s_w, B.PATH_AUTO)
+    assert _check_gemm(t, w, s_a, s_w, B.PATH_POPC, dirty_sign=True)
 
 
 @pytest.mark.parametrize("path", PATHS)
