@@ -22,7 +22,7 @@ PATH_AUTO, PATH_POPC, PATH_MFMA, PATH_FP4 = 0, 1, 2, 3
 
 EXPORTS = ["bwta_plane_row_words", "bwta_workspace_bytes", "bwta_quantize_pack_act",
            "bwta_pack_weights", "bwta_gemm", "bwta_linear", "bwta_strerror", "bwta_last_hip_error",
-           "bwta_set_path", "bwta_get_path", "bwta_auto_path", "bwta_version"]
+           "bwta_set_path", "bwta_get_path", "bwta_auto_path", "bwta_version", "bwta_set_tile"]
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -56,6 +56,8 @@ _lib.bwta_get_path.restype = _c.c_int
 _lib.bwta_auto_path.restype = _c.c_int
 _lib.bwta_auto_path.argtypes = [_c.c_int, _c.c_int, _c.c_int]
 _lib.bwta_version.restype = _c.c_int
+_lib.bwta_set_tile.restype = _c.c_int
+_lib.bwta_set_tile.argtypes = [_c.c_int]
 
 
 class BwtaError(RuntimeError):
@@ -122,6 +124,10 @@ def get_path():
 
 def auto_path(M, N, K):
     return int(_lib.bwta_auto_path(M, N, K))
+
+
+def set_tile(tile):
+    _check(_lib.bwta_set_tile(int(tile)))
 
 
 def version():

@@ -180,4 +180,10 @@ int bwta_auto_path(int M, int N, int K)
 
 int bwta_version(void) { return 1; }
 
+int bwta_set_tile(int tile)
+{
+    bwta::set_fp4_tile(tile);
+    return BWTA_OK;
+}
+
 }  // extern "C"

@@ -32,6 +32,7 @@ bool gemm_mfma_supported(const GemmArgs &g);
 hipError_t launch_gemm_mfma(const GemmArgs &g, hipStream_t st);
 
 size_t gemm_fp4_frag_bytes(int M, int K);
+void set_fp4_tile(int t);
 hipError_t launch_gemm_fp4(const GemmArgs &g, uint32_t *frag, hipStream_t st);
 
 // ---- device helpers -------------------------------------------------------------------------
@@ -49,24 +50,29 @@ __device__ __forceinline__ float load_scale(const ScaleArg &s, int row)
     return half_bits_to_float(s.ptr[s.mode == 1 ? 0 : row]);
 }
 
-// fp16( acc * s ) with a single rounding, where s = s_a * s_w is exact in fp32 (two 11-bit
-// significands).  acc is exact in fp32 (|acc| < 2^24); the fp32 product is rounded to odd using
-// the exact fma residual, so the final round-to-nearest-even to fp16 sees the true value.
-__device__ __forceinline__ uint16_t scaled_to_half(int acc, float s)
+// fp16( a * s ) with a single rounding.  a is an exact integer-valued float (|a| < 2^24) and
+// s = s_a * s_w is exact in fp32 (two 11-bit significands).  v_fma_mixlo_f16 / v_fma_mixhi_f16
+// evaluate the fused multiply-add exactly and round once, to nearest even, straight to fp16
+// (checked on MI355X against products whose fp32 rounding would sit on an fp16 tie).  The addend
+// is -0.0 so that a zero product keeps its sign.
+__device__ __forceinline__ uint32_t scaled_to_half2(float a0, float s0, float a1, float s1)
 {
-    float a = (float)acc;
-    float p = a * s;
-    float e = __builtin_fmaf(a, s, -p);
-    uint32_t b = __float_as_uint(p);
-    if (e != 0.0f && __builtin_fabsf(p) < __builtin_inff()) {
-        if ((e < 0.0f) != (p < 0.0f)) b -= 1u;  // true value lies towards zero from p
-        b |= 1u;
-    }
-    const _Float16 r = (_Float16)__uint_as_float(b);  // v_cvt_f16_f32, round to nearest even
-    uint16_t bits;
-    __builtin_memcpy(&bits, &r, 2);
-    return bits;
+    uint32_t r;
+    const float nz = -0.0f;
+    asm("v_fma_mixlo_f16 %0, %1, %2, %3" : "=v"(r) : "v"(a0), "v"(s0), "v"(nz));
+    asm("v_fma_mixhi_f16 %0, %1, %2, %3" : "+v"(r) : "v"(a1), "v"(s1), "v"(nz));
+    return r;  // low half = fp16(a0 * s0), high half = fp16(a1 * s1)
 }
+
+__device__ __forceinline__ uint16_t scaled_to_half(float a, float s)
+{
+    uint32_t r;
+    const float nz = -0.0f;
+    asm("v_fma_mixlo_f16 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(s), "v"(nz));
+    return (uint16_t)(r & 0xffffu);
+}
+
+__device__ __forceinline__ uint16_t scaled_to_half(int acc, float s) { return scaled_to_half((float)acc, s); }
 
 // Epilogue shared by the matrix-core kernels.  A wavefront owns WM x WN blocks of 32 x 32
 // accumulators in the MFMA layout (lane = column r32 of a block, register v = row

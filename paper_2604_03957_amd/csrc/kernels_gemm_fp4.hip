@@ -5,12 +5,16 @@
 // paper's arithmetic rules) while the instruction retires twice the MACs of the int8 form.
 //   * Activations are converted once per call from the two bit planes into E2M1 nibbles
 //     (bit 1 = mask, bit 3 = sign) in a fragment-major layout: [row block of 32][k step of
-//     64][lane][4 dwords], so a wavefront's operand is one contiguous kilobyte.
+//     64][lane][4 dwords].  A wavefront's operand for one instruction is one contiguous
+//     kilobyte, which it loads straight from global memory (L2) into registers, eight k steps
+//     ahead of use; activations never touch LDS.
 //   * Weights stay one bit each in HBM and LDS; a lane widens the 32 bits it needs for one
 //     instruction into four dwords of nibbles with three shifts and four and-or ops.
 // The dot product does not depend on the order of k inside an instruction, so element
 // 4 i + d of a 32-bit word goes to nibble i of dword d in BOTH operands, which is what makes
 // the widening that cheap.
+// The weights are the instruction's first operand, so a lane ends up with 4 consecutive output
+// channels of one token: the fp16 epilogue packs them and moves 8 bytes per LDS write.
 #include "bwta_internal.h"
 
 namespace bwta {
@@ -19,8 +23,6 @@ namespace {
 
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
-
-constexpr int W_PITCH = 12;  // dwords per LDS weight row: 8 words of a 256-k chunk + 4 pad
 
 // Which k step and lane half consume plane word q (identical rule in the converter and the GEMM):
 // words are taken in groups of 8 (one 256-k chunk); word j of a group feeds step 2*(j/4) + j%2
@@ -32,30 +34,27 @@ __device__ __forceinline__ void word_slot(int q, int &step, int &half)
     half = (j & 3) >> 1;
 }
 
-// planes -> E2M1 fragments.  One thread per (row, 4 words): 128-bit plane loads, and the 32 rows
-// of a row block sit on consecutive lanes so every 16-byte fragment store is part of a
-// contiguous 512-byte run.
+// planes -> E2M1 fragments.  A workgroup converts 32 rows x 32 words: plane rows are read with
+// coalesced 128-bit loads, the nibble dwords are regrouped through LDS, and the 16 KiB of
+// fragments it produces (16 k steps of one row block) leave as one contiguous run.  The buffer
+// is padded with zeros to a multiple of 8 row blocks and 8 k steps so that the GEMM never has
+// to guard an activation load.
 __global__ __launch_bounds__(256) void k_planes_to_fp4(const uint32_t *__restrict__ mask,
                                                        const uint32_t *__restrict__ sign, int M, int rw,
-                                                       int rows_padded, uint32_t *__restrict__ frag)
+                                                       int s_pad, uint32_t *__restrict__ frag)
 {
-    const int rw4 = rw >> 2;
-    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int64_t total = (int64_t)rows_padded * rw4;
-    if (gid >= total) return;
-    const int r = (int)(gid & 31);
-    const int64_t rest = gid >> 5;
-    const int q4 = (int)(rest % rw4);
-    const int rb = (int)(rest / rw4);
-    const int m = rb * 32 + r;
+    __shared__ uint4 tile[32 * 33];  // [slot = step_local * 2 + half][row], one spare row of skew
+    const int t = threadIdx.x;
+    const int rb = blockIdx.y, wc = blockIdx.x;  // row block, group of 32 words (16 k steps)
+    const int row = t >> 3, q4 = t & 7;
+    const int m = rb * 32 + row, q = 32 * wc + 4 * q4;
     uint4 mk4 = make_uint4(0, 0, 0, 0), sg4 = mk4;
-    if (m < M) {
-        mk4 = *(const uint4 *)(mask + (int64_t)m * rw + 4 * q4);
-        sg4 = *(const uint4 *)(sign + (int64_t)m * rw + 4 * q4);
+    if (m < M && q < rw) {
+        mk4 = *(const uint4 *)(mask + (int64_t)m * rw + q);
+        sg4 = *(const uint4 *)(sign + (int64_t)m * rw + q);
     }
     const uint32_t mks[4] = {mk4.x, mk4.y, mk4.z, mk4.w};
     const uint32_t sgs[4] = {sg4.x, sg4.y, sg4.z, sg4.w};
-    const int S = rw / 2;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
         const uint32_t mk = mks[w], sg = sgs[w] & mk;
@@ -65,12 +64,19 @@ __global__ __launch_bounds__(256) void k_planes_to_fp4(const uint32_t *__restric
         o.z = ((sg << 1) & 0x88888888u) | ((mk >> 1) & 0x22222222u);
         o.w = (sg & 0x88888888u) | ((mk >> 2) & 0x22222222u);
         int step, half;
-        word_slot(4 * q4 + w, step, half);
-        *(uint4 *)(frag + (((int64_t)rb * S + step) * 64 + half * 32 + r) * 4) = o;
+        word_slot(4 * q4 + w, step, half);  // local word index 0..31 -> local step 0..15
+        tile[(step * 2 + half) * 33 + row] = o;
+    }
+    __syncthreads();
+    uint4 *dst = (uint4 *)frag + ((int64_t)rb * s_pad + 16 * wc) * 64;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int idx = t + 256 * k;  // 16-byte piece of the 16 KiB output run: slot idx/32, row idx%32
+        if (16 * wc + (idx >> 6) < s_pad) dst[idx] = tile[(idx >> 5) * 33 + (idx & 31)];
     }
 }
 
-// weight bits -> E2M1 nibbles (+1 = 0b0010, -1 = 0b1010): element 4 i + d -> nibble i of dword d
+// weight bits -> E2M1 nibbles (+1 = 0b0010, -1 = 0b1010): element 4 i + d -> nibble i of dword d.
 // m88 = 0x88888888 and c22 = 0x22222222 are passed in registers the optimiser cannot see
 // through, so each dword is one v_and_or_b32 (VOP3 cannot carry two literals on this ISA).
 __device__ __forceinline__ v8i widen_w(uint32_t x, uint32_t m88, uint32_t c22)
@@ -84,76 +90,83 @@ __device__ __forceinline__ v8i widen_w(uint32_t x, uint32_t m88, uint32_t c22)
     return r;
 }
 
+constexpr int WD_PITCH = 20;  // dwords per LDS weight row: 16 words (512 k) + 4 pad
+
 template <int WM, int WN, int WAVES_M, int WAVES_N>
 struct Cfg {
     static constexpr int BM = 32 * WM * WAVES_M, BN = 32 * WN * WAVES_N;
     static constexpr int THREADS = 64 * WAVES_M * WAVES_N;
-    static constexpr int A_DW = (BM / 32) * 1024;  // 4 steps * 64 lanes * 4 dwords per row block
-    static constexpr int W_DW = BN * W_PITCH;
-    static constexpr int BUF_DW = A_DW + W_DW;
-    static constexpr int EPI_BYTES = BM * 4 + (THREADS / 64) * 32 * (32 * WN + 8) * 2;
-    static constexpr int SMEM_BYTES = 2 * BUF_DW * 4 > EPI_BYTES ? 2 * BUF_DW * 4 : EPI_BYTES;
-    static constexpr int A_PIECES = (BM / 32) * 256;  // 16-byte pieces per chunk
-    static constexpr int W_PIECES = BN * 2;
-    static constexpr int A_LOADS = (A_PIECES + THREADS - 1) / THREADS;
+    static constexpr int W_DW = BN * WD_PITCH;
+    static constexpr int W_PIECES = BN * 4;  // 16-byte pieces per 512 k
     static constexpr int W_LOADS = (W_PIECES + THREADS - 1) / THREADS;
+    static constexpr int STRIP_HALFS = 32 * (32 * WN + 8);  // per wavefront: 32 tokens x 32*WN channels
+    static constexpr int EPI_BYTES = BN * 4 + (THREADS / 64) * STRIP_HALFS * 2;
+    static constexpr int SMEM_BYTES = 2 * W_DW * 4 > EPI_BYTES ? 2 * W_DW * 4 : EPI_BYTES;
 };
 
-template <int WM, int WN, int WAVES_M, int WAVES_N>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N)
-__attribute__((amdgpu_waves_per_eu(WM * WN >= 16 ? 1 : 2, WM * WN >= 16 ? 1 : 2))) void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag,
-                                                                     int row_blocks)
+template <int WM, int WN, int WAVES_M, int WAVES_N, int OCC, bool WITH_ACC>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
+void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, int tiles_n, int tiles_total)
 {
     using C = Cfg<WM, WN, WAVES_M, WAVES_N>;
+    constexpr int D = 8;  // activation prefetch distance in k steps
     extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
+
+    // Workgroup ids are dealt round-robin to the 8 XCDs; give every XCD a contiguous range of
+    // tiles (whole strips of tokens) so that its L2 keeps re-serving the same activation rows.
+    int tile_id;
+    {
+        const int L = blockIdx.x, xcd = L & 7, k = L >> 3;
+        const int chunk = tiles_total >> 3, rem = tiles_total & 7;
+        tile_id = xcd * chunk + (xcd < rem ? xcd : rem) + k;
+    }
+    const int tm = tile_id / tiles_n, tn = tile_id - tm * tiles_n;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
     const int r32 = lane & 31, h = lane >> 5;
-    const int m0 = blockIdx.y * C::BM, n0 = blockIdx.x * C::BN;
-    const int rb0 = blockIdx.y * (C::BM / 32);
-    const int rw = g.rw, S = rw / 2;
-    const int nchunks = (rw + 7) / 8;
+    const int m0 = tm * C::BM, n0 = tn * C::BN;
+    const int rw = g.rw;
+    const int npairs = s_pad / 8;  // iterations of 8 k steps (512 k); the fragment buffer is padded to that
 
     uint32_t m88 = 0x88888888u, c22 = 0x22222222u;
     asm volatile("" : "+s"(m88));
     asm volatile("" : "+v"(c22));
 
-    uint4 pa[C::A_LOADS], pw[C::W_LOADS];
-
-    auto fetch = [&](int c) {
+    // this wavefront's activation fragments: row blocks rbw .. rbw+WM-1, one KiB per (block, step).
+    // Loads are never predicated: steps past the end are clamped to the last step (the value is
+    // loaded but never used).
+    const uint4 *abase = (const uint4 *)frag + ((int64_t)(tm * (C::BM / 32) + wm * WM) * s_pad) * 64 + lane;
+    const int last_step = s_pad - 1;
+    auto load_a = [&](uint4 (&dst)[WM], int step) {
+        const int st = step < last_step ? step : last_step;
 #pragma unroll
-        for (int i = 0; i < C::A_LOADS; ++i) {
-            const int p = tid + i * C::THREADS;  // piece: row block p/256, step (p%256)/64, lane p%64
-            const int rb = rb0 + (p >> 8), step = 4 * c + ((p >> 6) & 3);
-            pa[i] = make_uint4(0, 0, 0, 0);
-            if (p < C::A_PIECES && rb < row_blocks && step < S)
-                pa[i] = *(const uint4 *)(frag + (((int64_t)rb * S + step) * 64 + (p & 63)) * 4);
-        }
-#pragma unroll
-        for (int i = 0; i < C::W_LOADS; ++i) {
-            const int p = tid + i * C::THREADS;  // piece: row p/2, half p%2
-            const int n = n0 + (p >> 1), kw = 8 * c + 4 * (p & 1);
-            pw[i] = make_uint4(0, 0, 0, 0);
-            if (p < C::W_PIECES && n < g.N && kw < rw) pw[i] = *(const uint4 *)(g.wsign + (int64_t)n * rw + kw);
-        }
+        for (int i = 0; i < WM; ++i) dst[i] = abase[((int64_t)i * s_pad + st) * 64];
     };
 
-    auto stage = [&](int buf) {
-        uint32_t *sA = smem + buf * C::BUF_DW;
-        uint32_t *sW = sA + C::A_DW;
+    // weight words of 512 k; rows / words past the end are clamped (their products meet zero
+    // activations or land in channels that are never stored)
+    uint4 pw[C::W_LOADS];
+    auto fetch_w = [&](int pair) {
 #pragma unroll
-        for (int i = 0; i < C::A_LOADS; ++i) {
-            const int p = tid + i * C::THREADS;
-            if (p < C::A_PIECES) *(uint4 *)(sA + 4 * p) = pa[i];
+        for (int i = 0; i < C::W_LOADS; ++i) {
+            const int p = tid + i * C::THREADS;  // piece: row p/4, quarter p%4
+            int n = n0 + (p >> 2), kw = 16 * pair + 4 * (p & 3);
+            n = n < g.N ? n : g.N - 1;
+            kw = kw < rw ? kw : rw - 4;
+            if (C::W_PIECES % C::THREADS == 0 || p < C::W_PIECES)
+                pw[i] = *(const uint4 *)(g.wsign + (int64_t)n * rw + kw);
         }
+    };
+    auto stage_w = [&](int buf) {
+        uint32_t *sW = smem + buf * C::W_DW;
 #pragma unroll
         for (int i = 0; i < C::W_LOADS; ++i) {
             const int p = tid + i * C::THREADS;
-            if (p < C::W_PIECES) {
-                // chunk words w0..w7 are stored as [w0 w1 w4 w5 | w2 w3 w6 w7] so that lane half h
-                // finds the words of steps 0..3 in one 16-byte read at 4 h
-                uint32_t *row = sW + (p >> 1) * W_PITCH;
+            if (C::W_PIECES % C::THREADS == 0 || p < C::W_PIECES) {
+                // each chunk's words w0..w7 are stored as [w0 w1 w4 w5 | w2 w3 w6 w7] so that lane
+                // half h finds the words of its steps 0..3 in one 16-byte read at 4 h
+                uint32_t *row = sW + (p >> 2) * WD_PITCH + 8 * ((p >> 1) & 1);
                 const int half = p & 1;
                 *(uint2 *)(row + 2 * half) = make_uint2(pw[i].x, pw[i].y);
                 *(uint2 *)(row + 4 + 2 * half) = make_uint2(pw[i].z, pw[i].w);
@@ -161,102 +174,171 @@ __attribute__((amdgpu_waves_per_eu(WM * WN >= 16 ? 1 : 2, WM * WN >= 16 ? 1 : 2)
         }
     };
 
-    v16f acc[WM][WN];
+    v16f acc[WN][WM];  // [channel block][token block]: rows of the MFMA result are channels
 #pragma unroll
-    for (int i = 0; i < WM; ++i)
+    for (int j = 0; j < WN; ++j)
 #pragma unroll
-        for (int j = 0; j < WN; ++j)
+        for (int i = 0; i < WM; ++i)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+            for (int v = 0; v < 16; ++v) acc[j][i][v] = 0.0f;
 
-    fetch(0);
-    stage(0);
+    uint4 ring[D][WM];
+    fetch_w(0);
+#pragma unroll
+    for (int s = 0; s < D; ++s) load_a(ring[s], s);
+    stage_w(0);
     __syncthreads();
 
     int buf = 0;
-    for (int c = 0; c < nchunks; ++c) {
-        const bool more = c + 1 < nchunks;
-        if (more) fetch(c + 1);
-
-        const uint32_t *sA = smem + buf * C::BUF_DW;
-        const uint32_t *sW = sA + C::A_DW;
-        // always four steps: a short last chunk was staged with zeros, which add nothing
-        uint4 xw[WN];
+    for (int pr = 0; pr < npairs; ++pr) {
+        const uint32_t *sW = smem + buf * C::W_DW;
+        fetch_w(pr + 1 < npairs ? pr + 1 : pr);  // issued first: staging only waits for these
+        uint4 xw[2][WN];
 #pragma unroll
-        for (int j = 0; j < WN; ++j)
-            xw[j] = *(const uint4 *)(sW + ((wn * WN + j) * 32 + r32) * W_PITCH + 4 * h);
+        for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            {
-                v8i a[WM], b[WN];
+            for (int j = 0; j < WN; ++j)
+                xw[sub][j] = *(const uint4 *)(sW + ((wn * WN + j) * 32 + r32) * WD_PITCH + 8 * sub + 4 * h);
 #pragma unroll
-                for (int i = 0; i < WM; ++i) {
-                    const uint4 u = *(const uint4 *)(sA + (((wm * WM + i) * 4 + s) * 64 + lane) * 4);
-                    a[i][0] = (int)u.x; a[i][1] = (int)u.y; a[i][2] = (int)u.z; a[i][3] = (int)u.w;
-                    a[i][4] = a[i][5] = a[i][6] = a[i][7] = 0;
-                }
+        for (int s8 = 0; s8 < 8; ++s8) {
+            const int slot = s8 % D, sub = s8 >> 2, s = s8 & 3;
+            v8i a[WM], b[WN];
 #pragma unroll
-                for (int j = 0; j < WN; ++j)
-                    b[j] = widen_w(s == 0 ? xw[j].x : s == 1 ? xw[j].y : s == 2 ? xw[j].z : xw[j].w, m88, c22);
+            for (int i = 0; i < WM; ++i) {
+                a[i][0] = (int)ring[slot][i].x; a[i][1] = (int)ring[slot][i].y;
+                a[i][2] = (int)ring[slot][i].z; a[i][3] = (int)ring[slot][i].w;
+                a[i][4] = a[i][5] = a[i][6] = a[i][7] = 0;
+            }
+#pragma unroll
+            for (int j = 0; j < WN; ++j) {
+                const uint4 x = xw[sub][j];
+                b[j] = widen_w(s == 0 ? x.x : s == 1 ? x.y : s == 2 ? x.z : x.w, m88, c22);
+            }
+#pragma unroll
+            for (int j = 0; j < WN; ++j)
 #pragma unroll
                 for (int i = 0; i < WM; ++i)
-#pragma unroll
-                    for (int j = 0; j < WN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i], b[j], acc[i][j], 4, 4, 0,
-                                                                                    0, 0, 0);
-            }
+                    acc[j][i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b[j], a[i], acc[j][i], 4, 4, 0, 0, 0, 0);
+            load_a(ring[slot], 8 * pr + s8 + D);  // refill the slot D steps ahead
         }
-
-        if (more) stage(buf ^ 1);
+        stage_w(buf ^ 1);
         __syncthreads();
         buf ^= 1;
     }
 
-    // epilogue (the loop's last barrier has retired every LDS read, so the tiles can be reused)
-    float *sa_lds = (float *)smem;
-    uint16_t *strip = (uint16_t *)(smem + C::BM) + wave * (32 * (32 * WN + 8));
-    for (int t = tid; t < C::BM; t += C::THREADS) sa_lds[t] = (m0 + t < g.M) ? load_scale(g.s_a, m0 + t) : 0.0f;
+    // ---- epilogue.  Lane (r32, h) of block (j, i) holds token m = 32 i + r32 and channels
+    // n = 32 j + 8 g + 4 h + q (register v = 4 g + q).
+    const int m_wave = m0 + wm * WM * 32, n_wave = n0 + wn * WN * 32;
+    if (WITH_ACC && g.acc) {
+#pragma unroll
+        for (int i = 0; i < WM; ++i) {
+            const int m = m_wave + 32 * i + r32;
+#pragma unroll
+            for (int j = 0; j < WN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int n = n_wave + 32 * j + 8 * (v >> 2) + 4 * h + (v & 3);
+                    if (m < g.M && n < g.N) g.acc[(int64_t)m * g.N + n] = (int)acc[j][i][v];
+                }
+        }
+    }
+    if (!g.out) return;
+
+    float *sw_lds = (float *)smem;  // the loop's last barrier retired every read of the weight tiles
+    uint16_t *strip = (uint16_t *)(smem + C::BN) + wave * C::STRIP_HALFS;
+    constexpr int PITCH = 32 * WN + 8;  // halfs; 16-byte aligned rows, conflict-free 8-byte writes
+    for (int t = tid; t < C::BN; t += C::THREADS) sw_lds[t] = (n0 + t < g.N) ? load_scale(g.s_w, n0 + t) : 0.0f;
     __syncthreads();
-    store_wave_tile<WM, WN>(g, m0 + wm * WM * 32, n0 + wn * WN * 32, wm * WM * 32, strip, sa_lds,
-                            [&](int i, int j, int v) { return (int)acc[i][j][v]; });
+    const bool full = (m_wave + 32 * WM <= g.M) && (n_wave + 32 * WN <= g.N) && ((g.ldo & 7) == 0) &&
+                      (((uintptr_t)g.out & 15) == 0);
+    constexpr int LPR = 4 * WN, RPI = 64 / LPR;  // lanes per token row (8 halfs each), rows per store
+#pragma unroll
+    for (int i = 0; i < WM; ++i) {
+        const int m = m_wave + 32 * i + r32;
+        const float sa = m < g.M ? load_scale(g.s_a, m) : 0.0f;
+#pragma unroll
+        for (int j = 0; j < WN; ++j) {
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const int nl = 32 * j + 8 * gq + 4 * h;
+                const float4 sw = *(const float4 *)(sw_lds + wn * WN * 32 + nl);
+                uint2 hv;  // four consecutive channels of this token, exactly rounded
+                hv.x = scaled_to_half2(acc[j][i][4 * gq], sa * sw.x, acc[j][i][4 * gq + 1], sa * sw.y);
+                hv.y = scaled_to_half2(acc[j][i][4 * gq + 2], sa * sw.z, acc[j][i][4 * gq + 3], sa * sw.w);
+                *(uint2 *)(strip + r32 * PITCH + nl) = hv;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+        for (int rr = 0; rr < 32; rr += RPI) {
+            const int row = rr + lane / LPR, c8 = 8 * (lane % LPR);
+            const int mo = m_wave + 32 * i + row, n = n_wave + c8;
+            const uint4 q = *(const uint4 *)(strip + row * PITCH + c8);
+            uint16_t *dst = g.out + (int64_t)mo * g.ldo + n;
+            if (full) {
+                *(uint4 *)dst = q;
+            } else if (mo < g.M && n < g.N) {
+                const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (n + e < g.N) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    }
 }
 
-template <int WM, int WN, int WAVES_M, int WAVES_N>
-hipError_t launch(const GemmArgs &g, const uint32_t *frag, hipStream_t st)
+template <int WM, int WN, int WAVES_M, int WAVES_N, int OCC, bool WITH_ACC>
+hipError_t launch(const GemmArgs &g, const uint32_t *frag, int s_pad, hipStream_t st)
 {
     using C = Cfg<WM, WN, WAVES_M, WAVES_N>;
     static bool configured = false;  // benign race: setting the attribute twice is harmless
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_gemm_fp4<WM, WN, WAVES_M, WAVES_N>,
+        hipError_t e = hipFuncSetAttribute((const void *)k_gemm_fp4<WM, WN, WAVES_M, WAVES_N, OCC, WITH_ACC>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM_BYTES);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    dim3 grid((g.N + C::BN - 1) / C::BN, (g.M + C::BM - 1) / C::BM);
-    hipLaunchKernelGGL((k_gemm_fp4<WM, WN, WAVES_M, WAVES_N>), grid, dim3(C::THREADS), C::SMEM_BYTES, st, g, frag,
-                       (g.M + 31) / 32);
+    const int tiles_n = (g.N + C::BN - 1) / C::BN, tiles_m = (g.M + C::BM - 1) / C::BM;
+    const int64_t total = (int64_t)tiles_n * tiles_m;
+    if (total > 0x7fffffff) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((k_gemm_fp4<WM, WN, WAVES_M, WAVES_N, OCC, WITH_ACC>), dim3((unsigned)total), dim3(C::THREADS),
+                       C::SMEM_BYTES, st, g, frag, s_pad, tiles_n, (int)total);
     return hipGetLastError();
 }
 
 }  // namespace
 
+static int fp4_rb_pad(int M) { return ((M + 31) / 32 + 7) / 8 * 8; }
+static int fp4_s_pad(int rw) { return (rw / 2 + 7) / 8 * 8; }
+
 size_t gemm_fp4_frag_bytes(int M, int K)
 {
-    const size_t rw = 4 * (((size_t)K + 127) / 128);
-    return (size_t)((M + 31) / 32) * 32 * rw * 16;  // 4 bits per element of the padded matrix
+    const int rw = 4 * ((K + 127) / 128);
+    return (size_t)fp4_rb_pad(M) * fp4_s_pad(rw) * 1024;  // one KiB per (row block, k step)
 }
+
+static int g_fp4_tile = 0;
+void set_fp4_tile(int t) { g_fp4_tile = t; }
 
 hipError_t launch_gemm_fp4(const GemmArgs &g, uint32_t *frag, hipStream_t st)
 {
-    const int rows_padded = (g.M + 31) / 32 * 32;
-    const int64_t total = (int64_t)rows_padded * (g.rw / 4);
-    hipLaunchKernelGGL(k_planes_to_fp4, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, g.mask, g.sign,
-                       g.M, g.rw, rows_padded, frag);
+    const int rb_pad = fp4_rb_pad(g.M), s_pad = fp4_s_pad(g.rw);
+    hipLaunchKernelGGL(k_planes_to_fp4, dim3((s_pad + 15) / 16, rb_pad), dim3(256), 0, st, g.mask, g.sign, g.M,
+                       g.rw, s_pad, frag);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    auto tiles = [&](int bm, int bn) { return (int64_t)((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn); };
-    if (tiles(128, 256) >= 512) return launch<2, 4, 2, 2>(g, frag, st);
-    return launch<2, 2, 2, 2>(g, frag, st);
+    if (g.acc) return launch<2, 2, 2, 2, 2, true>(g, frag, s_pad, st);  // int32 output: test / debug path
+    switch (g_fp4_tile) {  // forced tile (tuning sweeps); 0 = heuristic below
+    case 22: return launch<2, 2, 2, 2, 2, false>(g, frag, s_pad, st);
+    case 23: return launch<2, 2, 2, 2, 3, false>(g, frag, s_pad, st);
+    case 24: return launch<2, 4, 2, 2, 2, false>(g, frag, s_pad, st);
+    case 42: return launch<4, 2, 2, 2, 2, false>(g, frag, s_pad, st);
+    default: break;
+    }
+    return launch<2, 2, 2, 2, 3, false>(g, frag, s_pad, st);
 }
 
 }  // namespace bwta

@@ -181,7 +181,11 @@ def test_gemm_degenerate_inputs(path):
     big = s_a.copy(); big[:] = np.float16(60000.0)                # overflow to +-Inf in the epilogue
     _check_gemm(t, w, big, s_w, path)
     tiny = s_w.copy(); tiny[:] = np.float16(2.0 ** -24)           # subnormal fp16 results
-    _check_gemm(t, w, np.full(M, 2.0 ** -10, np.float16), tiny, path)
+    assert _check_gemm(t, w, np.full(M, 2.0 ** -10, np.float16), tiny, path)
+    neg = s_a.copy(); neg[::2] *= -1                              # negative scales, signed zeros
+    sparse = t.copy(); sparse[:, 3:] = 0
+    assert _check_gemm(sparse, w, neg, s_w, path)
+    assert _check_gemm(t, w, neg, -s_w, path)
 
 
 @pytest.mark.parametrize("path", PATHS)
