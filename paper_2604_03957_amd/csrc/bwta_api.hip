@@ -37,7 +37,7 @@ int run_gemm(const bwta::GemmArgs &g, void *workspace, hipStream_t st)
     int path = resolve_path(g.M, g.N, g.K);
     if (path == BWTA_PATH_FP4) {
         uint32_t *frag = (uint32_t *)((char *)workspace + 2 * plane_bytes(g.M, g.K));
-        return hip_result(bwta::launch_gemm_fp4(g, frag, st));
+        return hip_result(bwta::launch_gemm_fp4(g, frag, false, st));
     }
     if (path == BWTA_PATH_MFMA && bwta::gemm_mfma_supported(g)) return hip_result(bwta::launch_gemm_mfma(g, st));
     if (bwta::gemv_popc_supported(g)) return hip_result(bwta::launch_gemv_popc(g, st));
@@ -135,6 +135,17 @@ int bwta_linear(const void *A, int64_t lda, const void *s_a, int a_scale_mode, c
     if (!workspace || workspace_bytes < bwta_workspace_bytes(M, N, K)) return BWTA_ERR_WORKSPACE;
     if (!aligned(workspace, 256)) return BWTA_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
+    if (resolve_path(M, N, K) == BWTA_PATH_FP4) {
+        // ternarise straight into the matrix-core operand layout; no bit planes on this route
+        uint32_t *frag = (uint32_t *)((char *)workspace + 2 * plane_bytes(M, K));
+        bwta::ScaleArg sa{(const uint16_t *)s_a, s_a ? a_scale_mode : BWTA_SCALE_NONE};
+        rc = hip_result(bwta::launch_quantize_to_fp4(A, lda, sa, M, K, frag, st));
+        if (rc != BWTA_OK) return rc;
+        bwta::GemmArgs g{nullptr, nullptr, wsign, M, N, K, (int)bwta_plane_row_words(K), sa,
+                         {(const uint16_t *)s_w, s_w ? w_scale_mode : BWTA_SCALE_NONE},
+                         nullptr, (uint16_t *)out, ldo};
+        return hip_result(bwta::launch_gemm_fp4(g, frag, true, st));
+    }
     uint32_t *mask = (uint32_t *)workspace;
     uint32_t *sign = (uint32_t *)((char *)workspace + plane_bytes(M, K));
     bwta::ScaleArg sa{(const uint16_t *)s_a, s_a ? a_scale_mode : BWTA_SCALE_NONE};

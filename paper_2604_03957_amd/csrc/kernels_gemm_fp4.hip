@@ -76,6 +76,60 @@ __global__ __launch_bounds__(256) void k_planes_to_fp4(const uint32_t *__restric
     }
 }
 
+// fp16 activations -> E2M1 fragments in one pass (ternarise by the paper's threshold rule and
+// emit the GEMM operand directly; no bit planes in between).  A lane takes 8 consecutive
+// elements (one 128-bit load); the 4 lanes of a quad cover one 32-element word, whose 4 nibble
+// dwords are assembled with a byte transpose inside the quad.  Quads of a wavefront walk
+// consecutive rows, so the 16-byte fragments they store are contiguous.
+__global__ __launch_bounds__(256) void k_quantize_to_fp4(const uint16_t *__restrict__ A, int64_t lda, ScaleArg s_a,
+                                                         int M, int K, int s_pad, uint32_t *__restrict__ frag,
+                                                         int vec_ok)
+{
+    const int t = threadIdx.x, lane = t & 63;
+    const int quad = t >> 2, j = t & 3;
+    const int row = quad & 31, q = 2 * blockIdx.x + (quad >> 5);  // row in block, plane word index
+    const int rb = blockIdx.y, m = rb * 32 + row;
+    const int k0 = 32 * q + 8 * j;
+    uint32_t V = 0;  // byte d = nibbles of elements d (low) and d + 4 (high): mask -> bit 1, sign -> bit 3
+    if (m < M && k0 < K) {
+        const uint16_t *src = A + (int64_t)m * lda + k0;
+        const int nvalid = K - k0 >= 8 ? 8 : K - k0;
+        uint16_t v[8];
+        if (nvalid == 8 && vec_ok) {
+            const uint4 x = *(const uint4 *)src;
+            v[0] = x.x & 0xffff; v[1] = x.x >> 16; v[2] = x.y & 0xffff; v[3] = x.y >> 16;
+            v[4] = x.z & 0xffff; v[5] = x.z >> 16; v[6] = x.w & 0xffff; v[7] = x.w >> 16;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = e < nvalid ? src[e] : (uint16_t)0;
+        }
+        const float s = load_scale(s_a, m);
+        const bool ok = (s > 0.0f) && (s < __builtin_inff());
+        const float hthr = 0.5f * s;  // exact
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float a = half_bits_to_float(v[e]);
+            const bool pos = a >= hthr, neg = a < -hthr;  // NaN fails both; pads are +0
+            const bool live = ok && e < nvalid;
+            const int base = 8 * (e & 3) + 4 * (e >> 2);
+            V |= (uint32_t)(live && (pos || neg)) << (base + 1);
+            V |= (uint32_t)(live && neg) << (base + 3);
+        }
+    }
+    // quad byte transpose: lane d of the quad collects byte d of every lane -> dword d of the word
+    const uint32_t x0 = __builtin_amdgcn_mov_dpp(V, 0x00, 0xf, 0xf, true);  // quad_perm [0,0,0,0]
+    const uint32_t x1 = __builtin_amdgcn_mov_dpp(V, 0x55, 0xf, 0xf, true);  // [1,1,1,1]
+    const uint32_t x2 = __builtin_amdgcn_mov_dpp(V, 0xaa, 0xf, 0xf, true);  // [2,2,2,2]
+    const uint32_t x3 = __builtin_amdgcn_mov_dpp(V, 0xff, 0xf, 0xf, true);  // [3,3,3,3]
+    const uint32_t sh = 8 * j;
+    const uint32_t D = ((x0 >> sh) & 0xffu) | (((x1 >> sh) & 0xffu) << 8) | (((x2 >> sh) & 0xffu) << 16) |
+                       (((x3 >> sh) & 0xffu) << 24);
+    (void)lane;
+    int step, half;
+    word_slot(q, step, half);
+    if (step < s_pad) frag[(((int64_t)rb * s_pad + step) * 64 + half * 32 + row) * 4 + j] = D;
+}
+
 // weight bits -> E2M1 nibbles (+1 = 0b0010, -1 = 0b1010): element 4 i + d -> nibble i of dword d.
 // m88 = 0x88888888 and c22 = 0x22222222 are passed in registers the optimiser cannot see
 // through, so each dword is one v_and_or_b32 (VOP3 cannot carry two literals on this ISA).
@@ -320,16 +374,31 @@ size_t gemm_fp4_frag_bytes(int M, int K)
     return (size_t)fp4_rb_pad(M) * fp4_s_pad(rw) * 1024;  // one KiB per (row block, k step)
 }
 
+// fp16 activations -> fragments (bwta_linear's first half on the FP4 path)
+hipError_t launch_quantize_to_fp4(const void *A, int64_t lda, ScaleArg s_a, int M, int K, uint32_t *frag,
+                                  hipStream_t st)
+{
+    const int rw = 4 * ((K + 127) / 128);
+    const int rb_pad = fp4_rb_pad(M), s_pad = fp4_s_pad(rw);
+    const int vec_ok = (((uintptr_t)A % 16) == 0 && (lda % 8) == 0) ? 1 : 0;
+    hipLaunchKernelGGL(k_quantize_to_fp4, dim3(s_pad, rb_pad), dim3(256), 0, st, (const uint16_t *)A, lda, s_a, M, K,
+                       s_pad, frag, vec_ok);
+    return hipGetLastError();
+}
+
 static int g_fp4_tile = 0;
 void set_fp4_tile(int t) { g_fp4_tile = t; }
 
-hipError_t launch_gemm_fp4(const GemmArgs &g, uint32_t *frag, hipStream_t st)
+// frag_ready: the fragments were already produced by launch_quantize_to_fp4 (planes unused)
+hipError_t launch_gemm_fp4(const GemmArgs &g, uint32_t *frag, bool frag_ready, hipStream_t st)
 {
     const int rb_pad = fp4_rb_pad(g.M), s_pad = fp4_s_pad(g.rw);
-    hipLaunchKernelGGL(k_planes_to_fp4, dim3((s_pad + 15) / 16, rb_pad), dim3(256), 0, st, g.mask, g.sign, g.M,
-                       g.rw, s_pad, frag);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    if (!frag_ready) {
+        hipLaunchKernelGGL(k_planes_to_fp4, dim3((s_pad + 15) / 16, rb_pad), dim3(256), 0, st, g.mask, g.sign, g.M,
+                           g.rw, s_pad, frag);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     if (g.acc) return launch<2, 2, 2, 2, 2, true>(g, frag, s_pad, st);  // int32 output: test / debug path
     switch (g_fp4_tile) {  // forced tile (tuning sweeps); 0 = heuristic below
     case 22: return launch<2, 2, 2, 2, 2, false>(g, frag, s_pad, st);

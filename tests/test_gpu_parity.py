@@ -234,3 +234,36 @@ def test_linear_laplace_block_input(path):
     _, _, want = oracle.linear(x, s, w, s_w)
     out = gpu_linear(x, s, gpu_pack_weights(w), s_w, 160, path=path)
     assert same_half(out, want)
+
+
+@pytest.mark.parametrize("path", PATHS)
+@pytest.mark.parametrize("M,N,K", [(1, 9, 40), (37, 130, 1001), (130, 70, 129), (257, 300, 2500), (33, 64, 11008)])
+def test_linear_ragged_shapes_and_special_values(M, N, K, path):
+    _say("linear ragged", M, N, K, "path", path)
+    A, s = _activation_case(300 + M, M, K)          # ties, NaN, Inf, -0.0 planted
+    if M > 4:
+        s[3] = np.float16(0.0)                      # an invalid scale zeroes the token
+    w = synth.binary_pm1(31, M + N, (N, K))
+    s_w = synth.scales(31, 5, N)
+    _, _, want = oracle.linear(A, s, w, s_w)
+    out = gpu_linear(A, s, gpu_pack_weights(w), s_w, N, path=path)
+    assert same_half(out, want)
+
+
+def test_linear_strided_input_and_output():
+    M, N, K, lda, ldo = 50, 72, 520, 528, 80
+    A, s = _activation_case(9, M, lda)
+    w = synth.binary_pm1(32, 1, (N, K))
+    s_w = synth.scales(32, 2, N)
+    _, _, want = oracle.linear(np.ascontiguousarray(A[:, :K]), s, w, s_w)
+    out = torch.full((M, ldo), 7.0, dtype=torch.float16, device="cuda:0")
+    ws = torch.empty(B.workspace_bytes(M, N, K), dtype=torch.uint8, device="cuda:0")
+    for path in PATHS:
+        B.set_path(path)
+        out.fill_(7.0)
+        B.bwta_linear(dev(A), dev(s), gpu_pack_weights(w), dev(s_w), out, ws, M=M, N=N, K=K, lda=lda, ldo=ldo)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        assert same_half(np.ascontiguousarray(got[:, :N]), want), path
+        assert np.all(got[:, N:] == 7.0)            # nothing written past N
+    B.set_path(B.PATH_AUTO)
