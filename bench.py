@@ -25,6 +25,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_INT8_TOPS = 5000.0   # MI355X dense int8 MFMA, TOP/s
+PEAK_FP4_TOPS = 10100.0   # MI355X dense fp4 MFMA, TFLOP/s (the dtype the dominant kernel contracts in)
 PEAK_HBM_GBS = 8000.0     # MI355X HBM3E, GB/s
 PEAK_VALU_POPC_TOPS = 1258.0  # 256 CU * 64 lanes * 2.4 GHz * 32 MAC per 2 VALU ops * 2 ops/MAC
 
@@ -51,6 +52,35 @@ def _event_ms(torch, fn, reps, warmup):
     return e0.elapsed_time(e1) / reps
 
 
+def _graph_of(torch, fn, check=None):
+    """Capture fn() (launches on the current stream only) into a HIP graph.  The replay is
+    checked against the eager result by `check` three times with eager work in between."""
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        fn()
+    torch.cuda.current_stream().wait_stream(s)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        fn()
+    torch.cuda.synchronize()
+    if check is not None:
+        for _ in range(3):
+            want = check(None)
+            fn()                      # eager
+            torch.cuda.synchronize()
+            want = check(None)
+            g.replay()
+            torch.cuda.synchronize()
+            check(want)
+    return g
+
+
+def _kernel_path_name(B, M, N, K):
+    return {B.PATH_MFMA: "mfma_int8", B.PATH_FP4: "mfma_fp4", B.PATH_POPC: "popc"}[B.auto_path(M, N, K)]
+
+
 class Layer:
     """One linear layer's device buffers."""
 
@@ -66,6 +96,7 @@ class Layer:
         del w
         self.out = torch.empty((M, N), dtype=torch.float16, device="cuda:0")
         self.ws = torch.empty(max(B.workspace_bytes(M, N, K), 256), dtype=torch.uint8, device="cuda:0")
+        self.prep = torch.empty(max(B.prepared_bytes(M, K), 256), dtype=torch.uint8, device="cuda:0")
         self.mask = torch.empty((M, self.rw), dtype=torch.int32, device="cuda:0")
         self.sign = torch.empty_like(self.mask)
         if from_fp16:
@@ -82,6 +113,12 @@ class Layer:
 
     def quantize(self, B):
         B.bwta_quantize_pack_act(self.A, self.s_a, self.mask, self.sign, None, M=self.M, K=self.K)
+
+    def prepare(self, B):  # first kernel of bwta_linear
+        B.bwta_prepare_act(self.A, self.s_a, self.prep, M=self.M, K=self.K)
+
+    def gemm_prepared(self, B):  # second kernel of bwta_linear
+        B.bwta_gemm_prepared(self.prep, self.wsign, self.s_a, self.s_w, None, self.out, M=self.M, N=self.N, K=self.K)
 
     def gemm(self, B):
         B.bwta_gemm(self.mask, self.sign, self.wsign, self.s_a, self.s_w, None, self.out, self.ws,
@@ -122,39 +159,49 @@ def run_c2(args, torch, B, synth):
         for L in layers:
             L.linear(B)
 
+    def check(want):
+        got = [L.out.clone() for L in layers]
+        if want is not None:
+            for a, b in zip(got, want):
+                assert torch.equal(a.view(torch.int16), b.view(torch.int16)), "graph replay differs from eager"
+        return got
+
+    run = step
+    if args.graph:
+        graph = _graph_of(torch, step, check)
+        run = graph.replay
     for _ in range(args.warmup):
-        step()
+        run()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        run()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt * 1e3 / args.steps
     ops = sum(L.ops for L in layers)
     value = ops / (ms_per_step * 1e-3) / 1e12
 
-    # per-kernel durations, HIP events on the launch stream
+    # per-kernel durations: HIP events on the launch stream around single-kernel entry points
     kern = []
     for L, c in zip(layers, cfgs):
-        tq = _event_ms(torch, lambda: L.quantize(B), args.steps, args.warmup)
-        tg = _event_ms(torch, lambda: L.gemm(B), args.steps, args.warmup)
-        kern.append({"layer": c["name"], "quantize_us": round(tq * 1e3, 2), "gemm_us": round(tg * 1e3, 2),
-                     "quantize_GBs": round(L.quantize_bytes() / (tq * 1e-3) / 1e9, 1),
-                     "gemm_TOPS": round(L.ops / (tg * 1e-3) / 1e12, 2),
-                     "path": {B.PATH_MFMA: "mfma_int8", B.PATH_FP4: "mfma_fp4", B.PATH_POPC: "popc"}[B.auto_path(L.M, L.N, L.K)]})
-    gemm_ms = [k["gemm_us"] / 1e3 for k in kern]
-    avg_gemm_ms = sum(gemm_ms) / len(gemm_ms)
+        tq = _event_ms(torch, lambda: L.prepare(B), args.steps, args.warmup)
+        tg = _event_ms(torch, lambda: L.gemm_prepared(B), args.steps, args.warmup)
+        kern.append({"layer": c["name"], "ternarize_us": round(tq * 1e3, 2), "gemm_us": round(tg * 1e3, 2),
+                     "ternarize_GBs": round((L.M * L.K * 2.5 + 2 * L.M) / (tq * 1e-3) / 1e9, 1),
+                     "gemm_TOPS": round(L.ops / (tg * 1e-3) / 1e12, 2), "path": _kernel_path_name(B, L.M, L.N, L.K)})
+    avg_gemm_ms = sum(k["gemm_us"] for k in kern) / len(kern) / 1e3
     achieved = (ops / len(layers)) / (avg_gemm_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "k_gemm_mfma (int8 MFMA product + epilogue), mean of the two layers",
-                "achieved": round(achieved, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
-                "frac": round(achieved / PEAK_INT8_TOPS, 4), "traffic": None}
+    roofline = {"bound": "mfma", "kernel": "k_gemm_fp4 (FP4 MFMA product + scale epilogue), mean of the two layers",
+                "achieved": round(achieved, 2), "peak": PEAK_FP4_TOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / PEAK_FP4_TOPS, 4), "frac_of_int8_peak": round(achieved / PEAK_INT8_TOPS, 4),
+                "traffic": None}
     out = {"metric": "BWTA linear effective TOPS (ternarize+pack+GEMM+epilogue), encoder FFN shapes",
            "value": round(value, 3), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
-           "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+           "vs_baseline": None, "dtype": "fp4 (E2M1 operands, exact integer result in fp32)", "data": "synthetic",
            "config": {"workload": "c2_ffn: M=4096 (32x128 tokens), K=768->N=3072 and K=3072->N=768, fp16 in/out",
-                      "path": "full (bwta_linear x2 per step)"},
+                      "path": "full (bwta_linear x2 per step)", "launch": "hip graph replay" if args.graph else "eager"},
            "roofline": roofline, "kernels": kern}
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline_c2(cfgs)
@@ -207,7 +254,8 @@ def run_c4(args, torch, B, synth):
                 for w in mats:
                     B.bwta_gemm(L.mask, L.sign, w, L.s_a, L.s_w, None, L.out, L.ws, M=L.M, N=L.N, K=L.K)
 
-            ms = _event_ms(torch, chain, max(2, args.steps // 4), 1) / nmat
+            run = _graph_of(torch, chain).replay if args.graph else chain
+            ms = _event_ms(torch, run, max(2, args.steps // 4), 1) / nmat
             gbs = L.gemm_bytes() / (ms * 1e-3) / 1e9
             r = dict(layer=c["name"], M=M, N=L.N, K=L.K, us_per_matrix=round(ms * 1e3, 2), GBs=round(gbs, 1),
                      frac_hbm=round(gbs / PEAK_HBM_GBS, 4))
@@ -249,6 +297,9 @@ def main():
     ap.add_argument("--workload", default="c2_ffn", choices=["c2_ffn", "c1_tiny", "c3_prefill", "c4_decode"])
     ap.add_argument("--decode-matrices", type=int, default=64)
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the step from a HIP graph instead of launching eagerly (eager is the default: "
+                         "the launch queue stays ahead of the GPU, and a 4-kernel graph replays no faster)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the BWTA hot path is a single-GPU kernel "

@@ -122,6 +122,23 @@ int bwta_linear(const void *A, int64_t lda, const void *s_a, int a_scale_mode,
                 void *out, int64_t ldo, void *workspace, size_t workspace_bytes,
                 bwta_stream_t stream);
 
+/*
+ * The two halves of bwta_linear as separate calls, so that one ternarisation can feed several
+ * weight matrices (Q/K/V, gate/up): bwta_prepare_act ternarises fp16 activations (same rule and
+ * arguments as bwta_quantize_pack_act with FP16 input) into `prepared`, an opaque device buffer
+ * of bwta_prepared_bytes(M, K) bytes, 256-byte aligned, laid out for whichever contraction
+ * kernel the current path selects for M tokens; bwta_gemm_prepared then computes
+ * out = fp16(s_w * s_a * (sign(W) (x) ternary(A))) from it exactly like bwta_gemm.  The path
+ * setting must not change between the two calls.  `prepared` is only read by the second call.
+ */
+size_t bwta_prepared_bytes(int M, int K);
+int bwta_prepare_act(const void *A, int64_t lda, const void *s_a, int a_scale_mode, int M, int K,
+                     void *prepared, size_t prepared_bytes, bwta_stream_t stream);
+int bwta_gemm_prepared(const void *prepared, size_t prepared_bytes, const uint32_t *wsign, int M,
+                       int N, int K, const void *s_a, int a_scale_mode, const void *s_w,
+                       int w_scale_mode, int32_t *acc, void *out, int64_t ldo,
+                       bwta_stream_t stream);
+
 /* Human-readable text for a return code (static storage). */
 const char *bwta_strerror(int code);
 /* hipError_t value behind the calling thread's most recent BWTA_ERR_HIP (0 if none). */

@@ -22,7 +22,8 @@ PATH_AUTO, PATH_POPC, PATH_MFMA, PATH_FP4 = 0, 1, 2, 3
 
 EXPORTS = ["bwta_plane_row_words", "bwta_workspace_bytes", "bwta_quantize_pack_act",
            "bwta_pack_weights", "bwta_gemm", "bwta_linear", "bwta_strerror", "bwta_last_hip_error",
-           "bwta_set_path", "bwta_get_path", "bwta_auto_path", "bwta_version", "bwta_set_tile"]
+           "bwta_set_path", "bwta_get_path", "bwta_auto_path", "bwta_version", "bwta_set_tile",
+           "bwta_prepared_bytes", "bwta_prepare_act", "bwta_gemm_prepared"]
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -47,6 +48,13 @@ _lib.bwta_gemm.argtypes = [_P, _P, _P, _c.c_int, _c.c_int, _c.c_int, _P, _c.c_in
 _lib.bwta_linear.restype = _c.c_int
 _lib.bwta_linear.argtypes = [_P, _c.c_int64, _P, _c.c_int, _P, _P, _c.c_int, _c.c_int, _c.c_int,
                              _c.c_int, _P, _c.c_int64, _P, _c.c_size_t, _P]
+_lib.bwta_prepared_bytes.restype = _c.c_size_t
+_lib.bwta_prepared_bytes.argtypes = [_c.c_int, _c.c_int]
+_lib.bwta_prepare_act.restype = _c.c_int
+_lib.bwta_prepare_act.argtypes = [_P, _c.c_int64, _P, _c.c_int, _c.c_int, _c.c_int, _P, _c.c_size_t, _P]
+_lib.bwta_gemm_prepared.restype = _c.c_int
+_lib.bwta_gemm_prepared.argtypes = [_P, _c.c_size_t, _P, _c.c_int, _c.c_int, _c.c_int, _P, _c.c_int, _P, _c.c_int,
+                                    _P, _P, _c.c_int64, _P]
 _lib.bwta_strerror.restype = _c.c_char_p
 _lib.bwta_strerror.argtypes = [_c.c_int]
 _lib.bwta_last_hip_error.restype = _c.c_int
@@ -165,3 +173,27 @@ def bwta_linear(A, s_a, wsign, s_w, out, workspace, *, M, N, K, lda=None, ldo=No
     _check(_lib.bwta_linear(_ptr(A), lda, _ptr(s_a), _mode(s_a, a_scale_mode), _ptr(wsign), _ptr(s_w),
                             _mode(s_w, w_scale_mode), M, N, K, _ptr(out), ldo, _ptr(workspace),
                             workspace_bytes, _stream(stream)))
+
+
+def _nbytes(buf, given):
+    if given is not None:
+        return given
+    return 0 if buf is None or isinstance(buf, int) else buf.numel() * buf.element_size()
+
+
+def prepared_bytes(M, K):
+    return int(_lib.bwta_prepared_bytes(M, K))
+
+
+def bwta_prepare_act(A, s_a, prepared, *, M, K, lda=None, a_scale_mode=None, prepared_bytes=None, stream=None):
+    lda = K if lda is None else lda
+    _check(_lib.bwta_prepare_act(_ptr(A), lda, _ptr(s_a), _mode(s_a, a_scale_mode), M, K, _ptr(prepared),
+                                 _nbytes(prepared, prepared_bytes), _stream(stream)))
+
+
+def bwta_gemm_prepared(prepared, wsign, s_a, s_w, acc, out, *, M, N, K, ldo=None, a_scale_mode=None,
+                       w_scale_mode=None, prepared_bytes=None, stream=None):
+    ldo = N if ldo is None else ldo
+    _check(_lib.bwta_gemm_prepared(_ptr(prepared), _nbytes(prepared, prepared_bytes), _ptr(wsign), M, N, K,
+                                   _ptr(s_a), _mode(s_a, a_scale_mode), _ptr(s_w), _mode(s_w, w_scale_mode),
+                                   _ptr(acc), _ptr(out), ldo, _stream(stream)))

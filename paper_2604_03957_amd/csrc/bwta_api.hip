@@ -28,7 +28,7 @@ size_t plane_bytes(int M, int K) { return round_up((size_t)M * (size_t)bwta_plan
 int resolve_path(int M, int N, int K)
 {
     int p = g_path.load(std::memory_order_relaxed);
-    return p == BWTA_PATH_AUTO ? bwta_auto_path(M, N, K) : p;
+    return p == BWTA_PATH_AUTO ? bwta_auto_path(M, N, K) : p;  // AUTO depends on M only
 }
 
 // workspace layout: [mask planes | sign planes | FP4 activation fragments]
@@ -134,27 +134,65 @@ int bwta_linear(const void *A, int64_t lda, const void *s_a, int a_scale_mode, c
     if (!aligned(A, 2) || !aligned(wsign, 16)) return BWTA_ERR_ALIGN;
     if (!workspace || workspace_bytes < bwta_workspace_bytes(M, N, K)) return BWTA_ERR_WORKSPACE;
     if (!aligned(workspace, 256)) return BWTA_ERR_ALIGN;
+    rc = bwta_prepare_act(A, lda, s_a, a_scale_mode, M, K, workspace, workspace_bytes, stream);
+    if (rc != BWTA_OK) return rc;
+    return bwta_gemm_prepared(workspace, workspace_bytes, wsign, M, N, K, s_a, a_scale_mode, s_w, w_scale_mode,
+                              nullptr, out, ldo, stream);
+}
+
+size_t bwta_prepared_bytes(int M, int K)
+{
+    if (M <= 0 || K <= 0) return 0;
+    return 2 * plane_bytes(M, K) + round_up(bwta::gemm_fp4_frag_bytes(M, K), 256);
+}
+
+int bwta_prepare_act(const void *A, int64_t lda, const void *s_a, int a_scale_mode, int M, int K,
+                     void *prepared, size_t prepared_bytes, bwta_stream_t stream)
+{
+    if (!scale_mode_ok(a_scale_mode)) return BWTA_ERR_UNSUPPORTED;
+    if (M < 0 || K < 0 || (M > 0 && K == 0)) return BWTA_ERR_SHAPE;
+    if (M == 0) return BWTA_OK;
+    if (lda < K) return BWTA_ERR_SHAPE;
+    if (!A) return BWTA_ERR_NULL;
+    if (a_scale_mode != BWTA_SCALE_NONE && !s_a) return BWTA_ERR_NULL;
+    if (!aligned(A, 2) || (s_a && !aligned(s_a, 2))) return BWTA_ERR_ALIGN;
+    if (!prepared || prepared_bytes < bwta_prepared_bytes(M, K)) return BWTA_ERR_WORKSPACE;
+    if (!aligned(prepared, 256)) return BWTA_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
-    if (resolve_path(M, N, K) == BWTA_PATH_FP4) {
-        // ternarise straight into the matrix-core operand layout; no bit planes on this route
-        uint32_t *frag = (uint32_t *)((char *)workspace + 2 * plane_bytes(M, K));
-        bwta::ScaleArg sa{(const uint16_t *)s_a, s_a ? a_scale_mode : BWTA_SCALE_NONE};
-        rc = hip_result(bwta::launch_quantize_to_fp4(A, lda, sa, M, K, frag, st));
-        if (rc != BWTA_OK) return rc;
-        bwta::GemmArgs g{nullptr, nullptr, wsign, M, N, K, (int)bwta_plane_row_words(K), sa,
-                         {(const uint16_t *)s_w, s_w ? w_scale_mode : BWTA_SCALE_NONE},
-                         nullptr, (uint16_t *)out, ldo};
+    bwta::ScaleArg sa{(const uint16_t *)s_a, s_a ? a_scale_mode : BWTA_SCALE_NONE};
+    if (resolve_path(M, 1, K) == BWTA_PATH_FP4) {
+        uint32_t *frag = (uint32_t *)((char *)prepared + 2 * plane_bytes(M, K));
+        return hip_result(bwta::launch_quantize_to_fp4(A, lda, sa, M, K, frag, st));
+    }
+    uint32_t *mask = (uint32_t *)prepared;
+    uint32_t *sign = (uint32_t *)((char *)prepared + plane_bytes(M, K));
+    return hip_result(bwta::launch_quantize_pack(A, BWTA_DTYPE_FP16, lda, sa, M, K, mask, sign, nullptr, st));
+}
+
+int bwta_gemm_prepared(const void *prepared, size_t prepared_bytes, const uint32_t *wsign, int M, int N, int K,
+                       const void *s_a, int a_scale_mode, const void *s_w, int w_scale_mode, int32_t *acc,
+                       void *out, int64_t ldo, bwta_stream_t stream)
+{
+    int rc = check_gemm_common(M, N, K, s_a, a_scale_mode, s_w, w_scale_mode, out, ldo);
+    if (rc != BWTA_OK) return rc;
+    if (M == 0 || N == 0) return BWTA_OK;
+    if (!wsign) return BWTA_ERR_NULL;
+    if (!acc && !out) return BWTA_ERR_NULL;
+    if (!aligned(wsign, 16) || (acc && !aligned(acc, 4))) return BWTA_ERR_ALIGN;
+    if (!prepared || prepared_bytes < bwta_prepared_bytes(M, K)) return BWTA_ERR_WORKSPACE;
+    if (!aligned(prepared, 256)) return BWTA_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    const uint32_t *mask = (const uint32_t *)prepared;
+    const uint32_t *sign = (const uint32_t *)((const char *)prepared + plane_bytes(M, K));
+    bwta::GemmArgs g{mask, sign, wsign, M, N, K, (int)bwta_plane_row_words(K),
+                     {(const uint16_t *)s_a, s_a ? a_scale_mode : BWTA_SCALE_NONE},
+                     {(const uint16_t *)s_w, s_w ? w_scale_mode : BWTA_SCALE_NONE},
+                     acc, (uint16_t *)out, ldo};
+    if (resolve_path(M, 1, K) == BWTA_PATH_FP4) {
+        uint32_t *frag = (uint32_t *)((char *)prepared + 2 * plane_bytes(M, K));
         return hip_result(bwta::launch_gemm_fp4(g, frag, true, st));
     }
-    uint32_t *mask = (uint32_t *)workspace;
-    uint32_t *sign = (uint32_t *)((char *)workspace + plane_bytes(M, K));
-    bwta::ScaleArg sa{(const uint16_t *)s_a, s_a ? a_scale_mode : BWTA_SCALE_NONE};
-    rc = hip_result(bwta::launch_quantize_pack(A, BWTA_DTYPE_FP16, lda, sa, M, K, mask, sign, nullptr, st));
-    if (rc != BWTA_OK) return rc;
-    bwta::GemmArgs g{mask, sign, wsign, M, N, K, (int)bwta_plane_row_words(K), sa,
-                     {(const uint16_t *)s_w, s_w ? w_scale_mode : BWTA_SCALE_NONE},
-                     nullptr, (uint16_t *)out, ldo};
-    return run_gemm(g, workspace, st);
+    return run_gemm(g, nullptr, st);
 }
 
 const char *bwta_strerror(int code)

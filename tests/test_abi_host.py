@@ -93,3 +93,19 @@ def test_gemm_and_linear_reject_bad_arguments():
     assert _code(lin, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, **dict(kw, lda=100)) == B.ERR_SHAPE
     assert _code(lin, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, **dict(kw, workspace_bytes=0)) == B.ERR_WORKSPACE
     lin(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, **dict(kw, M=0))
+
+
+def test_prepare_and_gemm_prepared_reject_bad_arguments():
+    pb = B.prepared_bytes(8, 128)
+    assert pb % 256 == 0 and pb > 0 and B.prepared_bytes(0, 128) == 0
+    kw = dict(M=8, K=128, stream=0, a_scale_mode=B.SCALE_VECTOR, prepared_bytes=pb)
+    assert _code(B.bwta_prepare_act, None, FAKE, FAKE, **kw) == B.ERR_NULL
+    assert _code(B.bwta_prepare_act, FAKE, FAKE, FAKE, **dict(kw, prepared_bytes=pb - 1)) == B.ERR_WORKSPACE
+    assert _code(B.bwta_prepare_act, FAKE, FAKE, FAKE + 32, **kw) == B.ERR_ALIGN
+    assert _code(B.bwta_prepare_act, FAKE, FAKE, FAKE, **dict(kw, lda=64)) == B.ERR_SHAPE
+    kw = dict(M=8, N=8, K=128, stream=0, a_scale_mode=B.SCALE_VECTOR, w_scale_mode=B.SCALE_VECTOR, prepared_bytes=pb)
+    g = B.bwta_gemm_prepared
+    assert _code(g, None, FAKE, FAKE, FAKE, None, FAKE, **kw) == B.ERR_WORKSPACE
+    assert _code(g, FAKE, None, FAKE, FAKE, None, FAKE, **kw) == B.ERR_NULL
+    assert _code(g, FAKE, FAKE, FAKE, FAKE, None, None, **kw) == B.ERR_NULL
+    assert _code(g, FAKE, FAKE, FAKE, FAKE, None, FAKE, **dict(kw, ldo=4)) == B.ERR_SHAPE

@@ -267,3 +267,25 @@ def test_linear_strided_input_and_output():
         assert same_half(np.ascontiguousarray(got[:, :N]), want), path
         assert np.all(got[:, N:] == 7.0)            # nothing written past N
     B.set_path(B.PATH_AUTO)
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_prepare_once_feed_several_weight_matrices(path):
+    M, K = 70, 1300
+    A, s = _activation_case(55, M, K)
+    prep = torch.empty(B.prepared_bytes(M, K), dtype=torch.uint8, device="cuda:0")
+    B.set_path(path)
+    try:
+        B.bwta_prepare_act(dev(A), dev(s), prep, M=M, K=K)
+        for i, N in enumerate((40, 129)):
+            w = synth.binary_pm1(60 + i, 1, (N, K))
+            s_w = synth.scales(60 + i, 2, N)
+            t, acc_want, want = oracle.linear(A, s, w, s_w)
+            out = torch.empty((M, N), dtype=torch.float16, device="cuda:0")
+            acc = torch.empty((M, N), dtype=torch.int32, device="cuda:0")
+            B.bwta_gemm_prepared(prep, gpu_pack_weights(w), dev(s), dev(s_w), acc, out, M=M, N=N, K=K)
+            torch.cuda.synchronize()
+            assert np.array_equal(acc.cpu().numpy(), acc_want)
+            assert same_half(out.cpu().numpy(), want)
+    finally:
+        B.set_path(B.PATH_AUTO)
