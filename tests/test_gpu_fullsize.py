@@ -1,0 +1,85 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times
+(path AUTO, fp16 output only), on sampled token rows the oracle computes one by one; decode
+shapes are compared in full."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import dev, gpu_pack_weights, same_half, workspace
+from paper_2604_03957_amd import binding as B
+from paper_2604_03957_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _rows(M, seed):
+    fixed = [0, 1, 31, 32, 63, 64, 127, 128, 129, 255, 256, M // 2, M - 129, M - 128, M - 2, M - 1]
+    rng = np.random.default_rng(seed)
+    rows = sorted(set(r for r in fixed if 0 <= r < M) | set(rng.integers(0, M, 12).tolist()))
+    return np.array(rows)
+
+
+@pytest.mark.parametrize("which", ["up", "down"])
+def test_config2_ffn_full_path_sampled_rows(which):
+    c = synth.config2(which)
+    M, N, K = c["M"], c["N"], c["K"]
+    print("config2", which, M, N, K, flush=True)
+    wsign = gpu_pack_weights(c["w"])
+    out = torch.empty((M, N), dtype=torch.float16, device="cuda:0")
+    B.bwta_linear(dev(c["A"]), dev(c["s_a"]), wsign, dev(c["s_w"]), out, workspace(M, N, K), M=M, N=N, K=K)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    rows = _rows(M, 1)
+    _, _, want = oracle.linear(c["A"][rows], c["s_a"][rows], c["w"], c["s_w"])
+    assert same_half(np.ascontiguousarray(got[rows]), want)
+    # properties that hold at any size: zero fraction of the ternarised input, output magnitude bound
+    assert np.all(np.abs(got.astype(np.float64)) <= K * 1.5 * c["s_a"].astype(np.float64).max() + 1)
+
+
+@pytest.mark.parametrize("which", ["qkvo", "upgate", "down"])
+def test_config3_prefill_gemm_sampled_rows(which):
+    c = synth.config3(which)
+    M, N, K = c["M"], c["N"], c["K"]
+    print("config3", which, M, N, K, flush=True)
+    rw = B.plane_row_words(K)
+    mask = torch.empty((M, rw), dtype=torch.int32, device="cuda:0")
+    sign = torch.empty_like(mask)
+    B.bwta_quantize_pack_act(dev(c["t"]), None, mask, sign, None, M=M, K=K, a_dtype=B.DTYPE_INT8)
+    wsign = gpu_pack_weights(c["w"])
+    out = torch.empty((M, N), dtype=torch.float16, device="cuda:0")
+    acc = torch.empty((M, N), dtype=torch.int32, device="cuda:0")
+    ws = workspace(M, N, K)
+    s_a, s_w = dev(c["s_a"]), dev(c["s_w"])
+    B.bwta_gemm(mask, sign, wsign, s_a, s_w, None, out, ws, M=M, N=N, K=K)     # as benchmarked
+    B.bwta_gemm(mask, sign, wsign, s_a, s_w, acc, None, ws, M=M, N=N, K=K)     # int32 accumulators
+    torch.cuda.synchronize()
+    rows = _rows(M, 2)
+    want_acc = oracle.gemm_unpacked(c["t"][rows], c["w"])
+    want_out = oracle.epilogue(want_acc, c["s_a"][rows], c["s_w"])
+    assert np.array_equal(acc.cpu().numpy()[rows], want_acc)
+    assert same_half(np.ascontiguousarray(out.cpu().numpy()[rows]), want_out)
+    # parity of every accumulator with its row's nonzero count (holds at any size)
+    nnz = np.count_nonzero(c["t"], axis=1)
+    a = acc.cpu().numpy()
+    assert np.all((a - nnz[:, None]) % 2 == 0) and np.all(np.abs(a) <= nnz[:, None])
+
+
+@pytest.mark.parametrize("which", ["upgate", "down"])
+@pytest.mark.parametrize("M", [1, 4, 16])
+def test_config4_decode_gemm_full(which, M):
+    c = synth.config4(which, M)
+    N, K = c["N"], c["K"]
+    print("config4", which, M, N, K, flush=True)
+    rw = B.plane_row_words(K)
+    mask = torch.empty((M, rw), dtype=torch.int32, device="cuda:0")
+    sign = torch.empty_like(mask)
+    B.bwta_quantize_pack_act(dev(c["t"]), None, mask, sign, None, M=M, K=K, a_dtype=B.DTYPE_INT8)
+    wsign = gpu_pack_weights(c["w"])
+    out = torch.empty((M, N), dtype=torch.float16, device="cuda:0")
+    acc = torch.empty((M, N), dtype=torch.int32, device="cuda:0")
+    B.bwta_gemm(mask, sign, wsign, dev(c["s_a"]), dev(c["s_w"]), acc, out, workspace(M, N, K), M=M, N=N, K=K)
+    torch.cuda.synchronize()
+    want_acc = oracle.gemm_unpacked(c["t"], c["w"])
+    assert np.array_equal(acc.cpu().numpy(), want_acc)
+    assert same_half(out.cpu().numpy(), oracle.epilogue(want_acc, c["s_a"], c["s_w"]))
