@@ -139,6 +139,24 @@ int bwta_gemm_prepared(const void *prepared, size_t prepared_bytes, const uint32
                        int w_scale_mode, int32_t *acc, void *out, int64_t ldo,
                        bwta_stream_t stream);
 
+/*
+ * Several BWTA products of ONE shape in one call (a decode step's independent matrices, expert
+ * groups, or a bandwidth measurement over many weight matrices).  `problems` is a HOST array of
+ * `count` records of DEVICE pointers with the meaning they have in bwta_gemm; scale modes, ldo
+ * and the workspace rule are shared (workspace: count * bwta_workspace_bytes(M, N, K) bytes,
+ * 256-byte aligned).  For M <= 8 all problems run in one kernel launch per 32 problems;
+ * otherwise the call is equivalent to `count` bwta_gemm calls.
+ */
+typedef struct bwta_gemm_problem {
+    const uint32_t *mask, *sign, *wsign;
+    const void *s_a, *s_w;
+    int32_t *acc;
+    void *out;
+} bwta_gemm_problem;
+int bwta_gemm_grouped(const bwta_gemm_problem *problems, int count, int M, int N, int K,
+                      int a_scale_mode, int w_scale_mode, int64_t ldo, void *workspace,
+                      size_t workspace_bytes, bwta_stream_t stream);
+
 /* Human-readable text for a return code (static storage). */
 const char *bwta_strerror(int code);
 /* hipError_t value behind the calling thread's most recent BWTA_ERR_HIP (0 if none). */

@@ -23,7 +23,7 @@ PATH_AUTO, PATH_POPC, PATH_MFMA, PATH_FP4 = 0, 1, 2, 3
 EXPORTS = ["bwta_plane_row_words", "bwta_workspace_bytes", "bwta_quantize_pack_act",
            "bwta_pack_weights", "bwta_gemm", "bwta_linear", "bwta_strerror", "bwta_last_hip_error",
            "bwta_set_path", "bwta_get_path", "bwta_auto_path", "bwta_version", "bwta_set_tile",
-           "bwta_prepared_bytes", "bwta_prepare_act", "bwta_gemm_prepared"]
+           "bwta_prepared_bytes", "bwta_prepare_act", "bwta_gemm_prepared", "bwta_gemm_grouped"]
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -55,6 +55,15 @@ _lib.bwta_prepare_act.argtypes = [_P, _c.c_int64, _P, _c.c_int, _c.c_int, _c.c_i
 _lib.bwta_gemm_prepared.restype = _c.c_int
 _lib.bwta_gemm_prepared.argtypes = [_P, _c.c_size_t, _P, _c.c_int, _c.c_int, _c.c_int, _P, _c.c_int, _P, _c.c_int,
                                     _P, _P, _c.c_int64, _P]
+
+
+class GemmProblem(_c.Structure):
+    _fields_ = [("mask", _P), ("sign", _P), ("wsign", _P), ("s_a", _P), ("s_w", _P), ("acc", _P), ("out", _P)]
+
+
+_lib.bwta_gemm_grouped.restype = _c.c_int
+_lib.bwta_gemm_grouped.argtypes = [_c.POINTER(GemmProblem), _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int,
+                                   _c.c_int64, _P, _c.c_size_t, _P]
 _lib.bwta_strerror.restype = _c.c_char_p
 _lib.bwta_strerror.argtypes = [_c.c_int]
 _lib.bwta_last_hip_error.restype = _c.c_int
@@ -197,3 +206,20 @@ def bwta_gemm_prepared(prepared, wsign, s_a, s_w, acc, out, *, M, N, K, ldo=None
     _check(_lib.bwta_gemm_prepared(_ptr(prepared), _nbytes(prepared, prepared_bytes), _ptr(wsign), M, N, K,
                                    _ptr(s_a), _mode(s_a, a_scale_mode), _ptr(s_w), _mode(s_w, w_scale_mode),
                                    _ptr(acc), _ptr(out), ldo, _stream(stream)))
+
+
+def make_problems(problems):
+    """problems: list of (mask, sign, wsign, s_a, s_w, acc, out) tensors/addresses -> ctypes array
+    (build once, reuse across calls)."""
+    arr = (GemmProblem * len(problems))()
+    for i, p in enumerate(problems):
+        for name, v in zip(("mask", "sign", "wsign", "s_a", "s_w", "acc", "out"), p):
+            setattr(arr[i], name, _ptr(v))
+    return arr
+
+
+def bwta_gemm_grouped(problem_array, workspace, *, M, N, K, a_scale_mode=SCALE_VECTOR, w_scale_mode=SCALE_VECTOR,
+                      ldo=None, workspace_bytes=None, stream=None):
+    ldo = N if ldo is None else ldo
+    _check(_lib.bwta_gemm_grouped(problem_array, len(problem_array), M, N, K, a_scale_mode, w_scale_mode, ldo,
+                                  _ptr(workspace), _nbytes(workspace, workspace_bytes), _stream(stream)))

@@ -195,6 +195,52 @@ int bwta_gemm_prepared(const void *prepared, size_t prepared_bytes, const uint32
     return run_gemm(g, nullptr, st);
 }
 
+int bwta_gemm_grouped(const bwta_gemm_problem *problems, int count, int M, int N, int K, int a_scale_mode,
+                      int w_scale_mode, int64_t ldo, void *workspace, size_t workspace_bytes, bwta_stream_t stream)
+{
+    if (count < 0) return BWTA_ERR_SHAPE;
+    if (count == 0) return BWTA_OK;
+    if (!problems) return BWTA_ERR_NULL;
+    const size_t per = bwta_workspace_bytes(M, N, K);
+    if (M > 0 && N > 0 && (!workspace || workspace_bytes < per * (size_t)count)) return BWTA_ERR_WORKSPACE;
+    if (workspace && !aligned(workspace, 256)) return BWTA_ERR_ALIGN;
+    for (int i = 0; i < count; ++i) {  // validate everything before enqueueing anything
+        const bwta_gemm_problem &p = problems[i];
+        int rc = check_gemm_common(M, N, K, p.s_a, p.s_a ? a_scale_mode : BWTA_SCALE_NONE, p.s_w,
+                                   p.s_w ? w_scale_mode : BWTA_SCALE_NONE, p.out, ldo);
+        if (rc != BWTA_OK) return rc;
+        if (M == 0 || N == 0) continue;
+        if (!p.mask || !p.sign || !p.wsign || (!p.acc && !p.out)) return BWTA_ERR_NULL;
+        if (!aligned(p.mask, 16) || !aligned(p.sign, 16) || !aligned(p.wsign, 16)) return BWTA_ERR_ALIGN;
+        if (p.acc && !aligned(p.acc, 4)) return BWTA_ERR_ALIGN;
+    }
+    if (M == 0 || N == 0) return BWTA_OK;
+    hipStream_t st = (hipStream_t)stream;
+    const int rw = (int)bwta_plane_row_words(K);
+    auto args_of = [&](const bwta_gemm_problem &p) {
+        return bwta::GemmArgs{p.mask, p.sign, p.wsign, M, N, K, rw,
+                              {(const uint16_t *)p.s_a, p.s_a ? a_scale_mode : BWTA_SCALE_NONE},
+                              {(const uint16_t *)p.s_w, p.s_w ? w_scale_mode : BWTA_SCALE_NONE},
+                              p.acc, (uint16_t *)p.out, ldo};
+    };
+    bwta::GemmArgs first = args_of(problems[0]);
+    if (resolve_path(M, N, K) == BWTA_PATH_POPC && bwta::gemv_popc_supported(first)) {
+        bwta::GemmArgs batch[32];
+        for (int base = 0; base < count; base += 32) {
+            const int n = count - base < 32 ? count - base : 32;
+            for (int i = 0; i < n; ++i) batch[i] = args_of(problems[base + i]);
+            int rc = hip_result(bwta::launch_gemv_popc_grouped(batch, n, st));
+            if (rc != BWTA_OK) return rc;
+        }
+        return BWTA_OK;
+    }
+    for (int i = 0; i < count; ++i) {
+        int rc = run_gemm(args_of(problems[i]), (char *)workspace + per * (size_t)i, st);
+        if (rc != BWTA_OK) return rc;
+    }
+    return BWTA_OK;
+}
+
 const char *bwta_strerror(int code)
 {
     switch (code) {

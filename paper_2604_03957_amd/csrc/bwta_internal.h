@@ -28,6 +28,7 @@ hipError_t launch_pack_weights(const void *W, int dtype, int64_t ldw, int N, int
 hipError_t launch_gemm_popc(const GemmArgs &g, hipStream_t st);
 bool gemv_popc_supported(const GemmArgs &g);
 hipError_t launch_gemv_popc(const GemmArgs &g, hipStream_t st);
+hipError_t launch_gemv_popc_grouped(const GemmArgs *gs, int count, hipStream_t st);
 bool gemm_mfma_supported(const GemmArgs &g);
 hipError_t launch_gemm_mfma(const GemmArgs &g, hipStream_t st);
 

@@ -289,3 +289,28 @@ def test_prepare_once_feed_several_weight_matrices(path):
             assert same_half(out.cpu().numpy(), want)
     finally:
         B.set_path(B.PATH_AUTO)
+
+
+@pytest.mark.parametrize("M,N,K,count", [(1, 300, 4096, 3), (4, 130, 11008, 2), (8, 70, 1000, 35), (16, 64, 512, 2)])
+def test_gemm_grouped_matches_oracle(M, N, K, count):
+    _say("grouped", M, N, K, count)
+    t, _, s_a, _ = _gemm_case(3000 + M, M, N, K, p0=0.5)
+    mask, sign, _ = oracle.pack_act(t)
+    dm, dsg, dsa = dev(mask), dev(sign), dev(s_a)
+    keep, probs, want = [], [], []
+    for i in range(count):
+        w = synth.binary_pm1(3100 + i, M, (N, K))
+        s_w = synth.scales(3200 + i, M, N)
+        acc_want = oracle.gemm_unpacked(t, w)
+        want.append((acc_want, oracle.epilogue(acc_want, s_a, s_w)))
+        dw, dsw = gpu_pack_weights(w), dev(s_w)
+        acc = torch.full((M, N), -9, dtype=torch.int32, device="cuda:0")
+        out = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda:0")
+        keep.append((dw, dsw, acc, out))
+        probs.append((dm, dsg, dw, dsa, dsw, acc, out))
+    ws = torch.empty(max(B.workspace_bytes(M, N, K), 256) * count, dtype=torch.uint8, device="cuda:0")
+    B.bwta_gemm_grouped(B.make_problems(probs), ws, M=M, N=N, K=K)
+    torch.cuda.synchronize()
+    for (dw, dsw, acc, out), (acc_want, out_want) in zip(keep, want):
+        assert np.array_equal(acc.cpu().numpy(), acc_want)
+        assert same_half(out.cpu().numpy(), out_want)
