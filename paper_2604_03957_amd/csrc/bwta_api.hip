@@ -270,13 +270,18 @@ int bwta_auto_path(int M, int N, int K)
 {
     (void)N;
     (void)K;
-    return M > 8 ? BWTA_PATH_FP4 : BWTA_PATH_POPC;
+    return M > 16 ? BWTA_PATH_FP4 : BWTA_PATH_POPC;
 }
 
 int bwta_version(void) { return 1; }
 
 int bwta_set_tile(int tile)
 {
+    if (tile >= 1000) {  // decode kernel: 1000 + 16 * lanes-per-row + chunks-per-lane
+        bwta::set_gemv_tile((tile - 1000) / 16, (tile - 1000) % 16);
+        return BWTA_OK;
+    }
+    bwta::set_gemv_tile(0, 0);
     bwta::set_fp4_tile(tile);
     return BWTA_OK;
 }

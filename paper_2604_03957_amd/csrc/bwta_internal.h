@@ -34,6 +34,7 @@ hipError_t launch_gemm_mfma(const GemmArgs &g, hipStream_t st);
 
 size_t gemm_fp4_frag_bytes(int M, int K);
 void set_fp4_tile(int t);
+void set_gemv_tile(int g, int nch);
 hipError_t launch_gemm_fp4(const GemmArgs &g, uint32_t *frag, bool frag_ready, hipStream_t st);
 hipError_t launch_quantize_to_fp4(const void *A, int64_t lda, ScaleArg s_a, int M, int K, uint32_t *frag,
                                   hipStream_t st);

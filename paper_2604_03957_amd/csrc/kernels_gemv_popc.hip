@@ -14,10 +14,21 @@ namespace bwta {
 
 namespace {
 
-__device__ __forceinline__ int popc4(const uint4 &m, const uint4 &s, const uint4 &w)
+// acc + popc(x): v_bcnt_u32_b32 accumulates for free; spelled out so the adds are not re-associated
+// into separate v_add3 instructions
+__device__ __forceinline__ int popc_acc(uint32_t x, int acc)
 {
-    return __popc(m.x & (s.x ^ w.x)) + __popc(m.y & (s.y ^ w.y)) + __popc(m.z & (s.z ^ w.z)) +
-           __popc(m.w & (s.w ^ w.w));
+    int r;
+    asm("v_bcnt_u32_b32 %0, %1, %2" : "=v"(r) : "v"(x), "v"(acc));
+    return r;
+}
+
+__device__ __forceinline__ int popc4(const uint4 &m, const uint4 &s, const uint4 &w, int acc)
+{
+    acc = popc_acc(m.x & (s.x ^ w.x), acc);
+    acc = popc_acc(m.y & (s.y ^ w.y), acc);
+    acc = popc_acc(m.z & (s.z ^ w.z), acc);
+    return popc_acc(m.w & (s.w ^ w.w), acc);
 }
 
 // sum over the G lanes of a group (G = 8, 16, 32 or 64 consecutive lanes); every lane gets the sum
@@ -55,68 +66,76 @@ __global__ __launch_bounds__(256) void k_gemv_popc(GemvBatch b, GemvShape sh)
     constexpr int RPP = 64 / G;  // rows per pass of one wavefront
     const int sub = lane / G, cl = lane % G;
     const int rw = sh.rw;
-    const uint4 zero4 = make_uint4(0, 0, 0, 0);
     const uint32_t *mask = b.mask[p], *sign = b.sign[p], *wsign = b.wsign[p];
 
-    bool valid[NCH];
+    // chunk j of this lane is cl + G j.  Chunks past the row end are clamped to the last chunk for
+    // the weight loads (never predicated) and get all-zero activation masks, so they add nothing.
+    int coff[NCH];  // dword offset of chunk j inside a row
 #pragma unroll
-    for (int j = 0; j < NCH; ++j) valid[j] = cl + G * j < sh.C4;
+    for (int j = 0; j < NCH; ++j) {
+        const int c = cl + G * j;
+        coff[j] = 4 * (c < sh.C4 ? c : sh.C4 - 1);
+    }
 
-    // this wavefront's weight rows: UNR passes, issued first (HBM latency), before the cache-resident activations
+    // weight rows of this wavefront: UNR passes, issued first (HBM latency); rows past N are
+    // clamped to the last row and never stored
     const int64_t row0 = ((int64_t)gw * UNR) * RPP + sub;
     uint4 w[UNR][NCH];
 #pragma unroll
     for (int u = 0; u < UNR; ++u) {
-        const int64_t n = row0 + (int64_t)u * RPP;
+        int64_t n = row0 + (int64_t)u * RPP;
+        n = n < sh.N ? n : sh.N - 1;
+        const uint32_t *wrow = wsign + n * rw;
 #pragma unroll
-        for (int j = 0; j < NCH; ++j) {
-            w[u][j] = zero4;
-            if (n < sh.N && valid[j]) w[u][j] = *(const uint4 *)(wsign + n * rw + 4 * (cl + G * j));
-        }
+        for (int j = 0; j < NCH; ++j) w[u][j] = *(const uint4 *)(wrow + coff[j]);
     }
 
-    // activation rows -> registers (tiny, cache resident)
+    // activation rows: staged once per workgroup in LDS (coalesced), then each lane keeps the
+    // chunks it needs in registers.  Layout: [token][plane][chunk] of 16 bytes.
+    extern __shared__ __attribute__((aligned(16))) uint4 s_act[];
+    for (int idx = threadIdx.x; idx < sh.M * 2 * sh.C4; idx += 256) {
+        const int c = idx % sh.C4, pl = (idx / sh.C4) & 1, m = idx / (2 * sh.C4);
+        s_act[idx] = *(const uint4 *)((pl ? sign : mask) + (int64_t)m * rw + 4 * c);
+    }
+    __syncthreads();
+    const uint4 zero4 = make_uint4(0, 0, 0, 0);
     uint4 am[MT][NCH], as[MT][NCH];
-    int nnz[MT];
+    int my_nnz = 0;  // nnz of token cl (the token this lane writes)
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
         int c = 0;
 #pragma unroll
         for (int j = 0; j < NCH; ++j) {
-            am[m][j] = zero4;
-            as[m][j] = zero4;
-            if (m < sh.M && valid[j]) {
-                am[m][j] = *(const uint4 *)(mask + (int64_t)m * rw + 4 * (cl + G * j));
-                as[m][j] = *(const uint4 *)(sign + (int64_t)m * rw + 4 * (cl + G * j));
-            }
-            c += __popc(am[m][j].x) + __popc(am[m][j].y) + __popc(am[m][j].z) + __popc(am[m][j].w);
+            const bool live = (m < sh.M) && (cl + G * j < sh.C4);
+            am[m][j] = live ? s_act[(2 * m) * sh.C4 + (coff[j] >> 2)] : zero4;
+            as[m][j] = s_act[(m < sh.M ? 2 * m + 1 : 1) * sh.C4 + (coff[j] >> 2)];
+            c = popc_acc(am[m][j].x, popc_acc(am[m][j].y, popc_acc(am[m][j].z, popc_acc(am[m][j].w, c))));
         }
-        nnz[m] = group_sum<G>(c);
+        c = group_sum<G>(c);
+        my_nnz = (cl == m) ? c : my_nnz;
     }
 
     const ScaleArg sa{b.s_a[p], b.s_a[p] ? sh.a_mode : 0}, sw{b.s_w[p], b.s_w[p] ? sh.w_mode : 0};
     int32_t *acc = b.acc[p];
     uint16_t *out = b.out[p];
+    const bool writer = cl < sh.M;  // lane cl of a group writes token cl (G >= 8 >= MT)
+    const float my_sa = writer ? load_scale(sa, cl) : 0.0f;
 #pragma unroll
     for (int u = 0; u < UNR; ++u) {
         const int64_t n = row0 + (int64_t)u * RPP;
-        int cnt[MT];
+        int my_cnt = 0;
 #pragma unroll
         for (int m = 0; m < MT; ++m) {
             int c = 0;
 #pragma unroll
-            for (int j = 0; j < NCH; ++j) c += popc4(am[m][j], as[m][j], w[u][j]);
-            cnt[m] = group_sum<G>(c);
+            for (int j = 0; j < NCH; ++j) c = popc4(am[m][j], as[m][j], w[u][j], c);
+            c = group_sum<G>(c);
+            my_cnt = (cl == m) ? c : my_cnt;
         }
-        if (n >= sh.N) continue;
-        const float swv = load_scale(sw, (int)n);
-#pragma unroll
-        for (int m = 0; m < MT; ++m) {
-            if (m < sh.M && m == cl) {  // lane m of the group writes token m (G >= 8 >= MT)
-                const int a = nnz[m] - 2 * cnt[m];
-                if (acc) acc[(int64_t)m * sh.N + n] = a;
-                if (out) out[(int64_t)m * sh.ldo + n] = scaled_to_half(a, load_scale(sa, m) * swv);
-            }
+        if (writer && n < sh.N) {
+            const int a = my_nnz - 2 * my_cnt;
+            if (acc) acc[(int64_t)cl * sh.N + n] = a;
+            if (out) out[(int64_t)cl * sh.ldo + n] = scaled_to_half(a, my_sa * load_scale(sw, (int)n));
         }
     }
 }
@@ -131,29 +150,36 @@ hipError_t launch_t(const GemvBatch &b, int count, const GemvShape &sh, hipStrea
     const int64_t passes = ((int64_t)sh.N + RPP - 1) / RPP;
     const int64_t waves = (passes + UNR - 1) / UNR;
     const unsigned grid = (unsigned)((waves + 3) / 4);
-    hipLaunchKernelGGL((k_gemv_popc<MT, G, NCH, UNR>), dim3(grid, count), dim3(256), 0, st, b, sh);
+    const size_t lds = (size_t)sh.M * 2 * sh.C4 * 16;  // <= 8 * 2 * 128 * 16 = 32 KiB
+    hipLaunchKernelGGL((k_gemv_popc<MT, G, NCH, UNR>), dim3(grid, count), dim3(256), lds, st, b, sh);
     return hipGetLastError();
 }
+
+int g_force_g = 0, g_force_nch = 0;  // tuning override (bwta_set_tile)
 
 template <int MT>
 hipError_t launch_m(const GemvBatch &b, int count, const GemvShape &sh, hipStream_t st)
 {
-    // smallest group that keeps the activation rows within ~128 registers: MT * NCH <= 16
+#define BWTA_GEMV_FORCE(G_, NCH_)                                                                  \
+    if constexpr (MT * NCH_ <= 16) {                                                               \
+        if (g_force_g == G_ && g_force_nch == NCH_ && sh.C4 <= G_ * NCH_)                          \
+            return launch_t<MT, G_, NCH_>(b, count, sh, st);                                       \
+    }
+    BWTA_GEMV_FORCE(8, 4) BWTA_GEMV_FORCE(16, 2) BWTA_GEMV_FORCE(32, 1) BWTA_GEMV_FORCE(16, 6)
+    BWTA_GEMV_FORCE(32, 3) BWTA_GEMV_FORCE(64, 2) BWTA_GEMV_FORCE(8, 11) BWTA_GEMV_FORCE(16, 4)
+    BWTA_GEMV_FORCE(32, 2) BWTA_GEMV_FORCE(64, 1) BWTA_GEMV_FORCE(32, 4)
+#undef BWTA_GEMV_FORCE
+    // Measured on MI355X: few chunks per lane (small activation register footprint, more
+    // wavefronts in flight) beats few lanes per row, so rows are spread over up to 32 lanes
+    // before a lane takes a second chunk; 64 lanes only when the registers demand it.
     const int C4 = sh.C4;
-    constexpr int CAP = 16 / MT;  // chunks per lane allowed
+    constexpr int CAP = 16 / MT;  // chunks per lane allowed (activation rows <= 128 registers)
 #define BWTA_GEMV_TRY(G_, NCH_)                                                    \
     if constexpr (NCH_ <= CAP) {                                                  \
         if (C4 <= G_ * NCH_) return launch_t<MT, G_, NCH_>(b, count, sh, st);     \
     }
     BWTA_GEMV_TRY(8, 1)
-    BWTA_GEMV_TRY(8, 2)
-    BWTA_GEMV_TRY(8, 4)
-    BWTA_GEMV_TRY(16, 4)
-    BWTA_GEMV_TRY(8, 11)
-    BWTA_GEMV_TRY(8, 16)
-    BWTA_GEMV_TRY(16, 2)
-    BWTA_GEMV_TRY(16, 6)
-    BWTA_GEMV_TRY(16, 8)
+    BWTA_GEMV_TRY(16, 1)
     BWTA_GEMV_TRY(32, 1)
     BWTA_GEMV_TRY(32, 2)
     BWTA_GEMV_TRY(32, 3)
@@ -174,39 +200,45 @@ hipError_t launch_any(const GemvBatch &b, int count, const GemvShape &sh, hipStr
 
 }  // namespace
 
-// M <= 8 tokens and K <= 16384 (at most two 16-byte chunks per lane at the widest group).
-bool gemv_popc_supported(const GemmArgs &g) { return g.M >= 1 && g.M <= 8 && g.rw / 4 <= 128 && g.N >= 1; }
+// M <= 16 tokens (more than 8 run as two token groups over the same weights) and K <= 16384
+// (at most two 16-byte chunks per lane at the widest group).
+bool gemv_popc_supported(const GemmArgs &g) { return g.M >= 1 && g.M <= 16 && g.rw / 4 <= 128 && g.N >= 1; }
 
-hipError_t launch_gemv_popc(const GemmArgs &g, hipStream_t st)
-{
-    GemvBatch b;
-    b.mask[0] = g.mask; b.sign[0] = g.sign; b.wsign[0] = g.wsign;
-    b.s_a[0] = g.s_a.mode ? g.s_a.ptr : nullptr;
-    b.s_w[0] = g.s_w.mode ? g.s_w.ptr : nullptr;
-    b.acc[0] = g.acc; b.out[0] = g.out;
-    GemvShape sh{g.M, g.N, g.rw, g.rw / 4, g.s_a.mode, g.s_w.mode, g.ldo};
-    return launch_any(b, 1, sh, st);
-}
-
-// count problems of one shape; pointers given as host arrays of device pointers
+// count problems of one shape; tokens beyond 8 become a second batch entry on the same weights
 hipError_t launch_gemv_popc_grouped(const GemmArgs *gs, int count, hipStream_t st)
 {
-    for (int base = 0; base < count; base += GemvBatch::MAX) {
-        const int n = count - base < GemvBatch::MAX ? count - base : GemvBatch::MAX;
-        GemvBatch b;
-        for (int i = 0; i < n; ++i) {
-            const GemmArgs &g = gs[base + i];
-            b.mask[i] = g.mask; b.sign[i] = g.sign; b.wsign[i] = g.wsign;
-            b.s_a[i] = g.s_a.mode ? g.s_a.ptr : nullptr;
-            b.s_w[i] = g.s_w.mode ? g.s_w.ptr : nullptr;
-            b.acc[i] = g.acc; b.out[i] = g.out;
+    const GemmArgs &g0 = gs[0];
+    const int groups = g0.M > 8 ? 2 : 1;
+    const int per_launch = GemvBatch::MAX / groups;
+    for (int base = 0; base < count; base += per_launch) {
+        const int n = count - base < per_launch ? count - base : per_launch;
+        for (int tg = 0; tg < groups; ++tg) {  // token groups of equal size launch together
+            const int m0 = 8 * tg, mt = (g0.M - m0) < 8 ? (g0.M - m0) : 8;
+            GemvBatch b;
+            for (int i = 0; i < n; ++i) {
+                const GemmArgs &g = gs[base + i];
+                b.mask[i] = g.mask + (int64_t)m0 * g.rw;
+                b.sign[i] = g.sign + (int64_t)m0 * g.rw;
+                b.wsign[i] = g.wsign;
+                b.s_a[i] = g.s_a.mode ? g.s_a.ptr + (g.s_a.mode == 2 ? m0 : 0) : nullptr;
+                b.s_w[i] = g.s_w.mode ? g.s_w.ptr : nullptr;
+                b.acc[i] = g.acc ? g.acc + (int64_t)m0 * g.N : nullptr;
+                b.out[i] = g.out ? g.out + (int64_t)m0 * g.ldo : nullptr;
+            }
+            GemvShape sh{mt, g0.N, g0.rw, g0.rw / 4, g0.s_a.mode, g0.s_w.mode, g0.ldo};
+            hipError_t e = launch_any(b, n, sh, st);
+            if (e != hipSuccess) return e;
         }
-        const GemmArgs &g0 = gs[base];
-        GemvShape sh{g0.M, g0.N, g0.rw, g0.rw / 4, g0.s_a.mode, g0.s_w.mode, g0.ldo};
-        hipError_t e = launch_any(b, n, sh, st);
-        if (e != hipSuccess) return e;
     }
     return hipSuccess;
+}
+
+hipError_t launch_gemv_popc(const GemmArgs &g, hipStream_t st) { return launch_gemv_popc_grouped(&g, 1, st); }
+
+void set_gemv_tile(int g, int nch)
+{
+    g_force_g = g;
+    g_force_nch = nch;
 }
 
 }  // namespace bwta

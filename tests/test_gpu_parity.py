@@ -153,7 +153,7 @@ def test_gemm_matches_oracle(M, N, K, path):
 
 DECODE_SHAPES = [(1, 7, 33), (2, 130, 128), (3, 257, 1000), (1, 1001, 4096), (4, 999, 4096), (8, 300, 4096),
                  (5, 258, 8192), (1, 515, 11008), (4, 130, 11008), (8, 67, 11008), (2, 70, 16384),
-                 (3, 40, 16512)]
+                 (3, 40, 16512), (9, 100, 4096), (13, 77, 1408), (16, 257, 11008), (16, 90, 768)]
 
 
 @pytest.mark.parametrize("M,N,K", DECODE_SHAPES)
