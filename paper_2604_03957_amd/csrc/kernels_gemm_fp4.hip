@@ -331,7 +331,9 @@ void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, int ti
             const uint4 q = *(const uint4 *)(strip + row * PITCH + c8);
             uint16_t *dst = g.out + (int64_t)mo * g.ldo + n;
             if (full) {
-                *(uint4 *)dst = q;
+                typedef unsigned v4u __attribute__((ext_vector_type(4)));
+                const v4u qv = {q.x, q.y, q.z, q.w};
+                __builtin_nontemporal_store(qv, (v4u *)dst);  // streamed once, never re-read here
             } else if (mo < g.M && n < g.N) {
                 const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
@@ -405,8 +407,13 @@ hipError_t launch_gemm_fp4(const GemmArgs &g, uint32_t *frag, bool frag_ready, h
     case 23: return launch<2, 2, 2, 2, 3, false>(g, frag, s_pad, st);
     case 24: return launch<2, 4, 2, 2, 2, false>(g, frag, s_pad, st);
     case 42: return launch<4, 2, 2, 2, 2, false>(g, frag, s_pad, st);
+    case 21: return launch<2, 1, 2, 2, 3, false>(g, frag, s_pad, st);
+    case 12: return launch<1, 2, 2, 2, 3, false>(g, frag, s_pad, st);
+    case 11: return launch<1, 1, 2, 2, 4, false>(g, frag, s_pad, st);
     default: break;
     }
+    // measured: long K runs best with 2 wavefronts per SIMD (179 registers), short K with 3
+    if (g.K >= 2048) return launch<2, 2, 2, 2, 2, false>(g, frag, s_pad, st);
     return launch<2, 2, 2, 2, 3, false>(g, frag, s_pad, st);
 }
 
