@@ -15,6 +15,8 @@
 // the widening that cheap.
 // The weights are the instruction's first operand, so a lane ends up with 4 consecutive output
 // channels of one token: the fp16 epilogue packs them and moves 8 bytes per LDS write.
+#include <type_traits>
+
 #include "bwta_internal.h"
 
 namespace bwta {
@@ -146,24 +148,32 @@ __device__ __forceinline__ v8i widen_w(uint32_t x, uint32_t m88, uint32_t c22)
 
 constexpr int WD_PITCH = 20;  // dwords per LDS weight row: 16 words (512 k) + 4 pad
 
-template <int WM, int WN, int WAVES_M, int WAVES_N>
+// KS > 1: the K loop is split over KS groups of wavefronts inside the workgroup (each group owns
+// every KS-th 512-k slab); their partial accumulators are summed through LDS before the epilogue.
+// Used when a shape has too few output tiles to fill the chip.
+template <int WM, int WN, int WAVES_M, int WAVES_N, int KS>
 struct Cfg {
     static constexpr int BM = 32 * WM * WAVES_M, BN = 32 * WN * WAVES_N;
-    static constexpr int THREADS = 64 * WAVES_M * WAVES_N;
-    static constexpr int W_DW = BN * WD_PITCH;
-    static constexpr int W_PIECES = BN * 4;  // 16-byte pieces per 512 k
+    static constexpr int GROUP_WAVES = WAVES_M * WAVES_N;
+    static constexpr int THREADS = 64 * GROUP_WAVES * KS;
+    static constexpr int W_DW = BN * WD_PITCH;           // one group's 512-k slab
+    static constexpr int W_PIECES = BN * 4 * KS;         // 16-byte pieces per iteration
     static constexpr int W_LOADS = (W_PIECES + THREADS - 1) / THREADS;
     static constexpr int STRIP_HALFS = 32 * (32 * WN + 8);  // per wavefront: 32 tokens x 32*WN channels
-    static constexpr int EPI_BYTES = BN * 4 + (THREADS / 64) * STRIP_HALFS * 2;
-    static constexpr int SMEM_BYTES = 2 * W_DW * 4 > EPI_BYTES ? 2 * W_DW * 4 : EPI_BYTES;
+    static constexpr int EPI_BYTES = BN * 4 + GROUP_WAVES * STRIP_HALFS * 2;
+    static constexpr int RED_BYTES = KS > 1 ? GROUP_WAVES * WM * WN * 16 * 64 * 4 : 0;
+    static constexpr int LOOP_BYTES = 2 * KS * W_DW * 4;
+    static constexpr int SMEM_BYTES =
+        (LOOP_BYTES > EPI_BYTES ? LOOP_BYTES : EPI_BYTES) > RED_BYTES ? (LOOP_BYTES > EPI_BYTES ? LOOP_BYTES : EPI_BYTES)
+                                                                      : RED_BYTES;
 };
 
-template <int WM, int WN, int WAVES_M, int WAVES_N, int OCC, bool WITH_ACC>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
+template <int WM, int WN, int WAVES_M, int WAVES_N, int OCC, bool WITH_ACC, int KS, int D>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KS) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
 void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, int tiles_n, int tiles_total)
 {
-    using C = Cfg<WM, WN, WAVES_M, WAVES_N>;
-    constexpr int D = 8;  // activation prefetch distance in k steps
+    using C = Cfg<WM, WN, WAVES_M, WAVES_N, KS>;
+    static_assert(D == 8 || D == 16, "activation prefetch distance in k steps: one or two slabs");
     extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
 
     // Workgroup ids are dealt round-robin to the 8 XCDs; give every XCD a contiguous range of
@@ -177,11 +187,14 @@ void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, int ti
     const int tm = tile_id / tiles_n, tn = tile_id - tm * tiles_n;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int kg = KS == 1 ? 0 : wave / C::GROUP_WAVES;  // k group
+    const int wl = KS == 1 ? wave : wave % C::GROUP_WAVES;  // wavefront within the group
+    const int wm = wl / WAVES_N, wn = wl % WAVES_N;
     const int r32 = lane & 31, h = lane >> 5;
     const int m0 = tm * C::BM, n0 = tn * C::BN;
     const int rw = g.rw;
-    const int npairs = s_pad / 8;  // iterations of 8 k steps (512 k); the fragment buffer is padded to that
+    const int npairs = s_pad / 8;  // slabs of 8 k steps (512 k); the fragment buffer is padded to that
+    const int niter = (npairs + KS - 1) / KS;
 
     uint32_t m88 = 0x88888888u, c22 = 0x22222222u;
     asm volatile("" : "+s"(m88));
@@ -201,11 +214,12 @@ void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, int ti
     // weight words of 512 k; rows / words past the end are clamped (their products meet zero
     // activations or land in channels that are never stored)
     uint4 pw[C::W_LOADS];
-    auto fetch_w = [&](int pair) {
+    auto fetch_w = [&](int it) {  // slabs it*KS .. it*KS+KS-1, one per k group
 #pragma unroll
         for (int i = 0; i < C::W_LOADS; ++i) {
-            const int p = tid + i * C::THREADS;  // piece: row p/4, quarter p%4
-            int n = n0 + (p >> 2), kw = 16 * pair + 4 * (p & 3);
+            const int p = tid + i * C::THREADS;  // piece: group p/(4 BN), row (p/4)%BN, quarter p%4
+            int n = n0 + (KS == 1 ? (p >> 2) : ((p >> 2) % C::BN));
+            int kw = 16 * (it * KS + (KS == 1 ? 0 : p / (4 * C::BN))) + 4 * (p & 3);
             n = n < g.N ? n : g.N - 1;
             kw = kw < rw ? kw : rw - 4;
             if (C::W_PIECES % C::THREADS == 0 || p < C::W_PIECES)
@@ -213,14 +227,14 @@ void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, int ti
         }
     };
     auto stage_w = [&](int buf) {
-        uint32_t *sW = smem + buf * C::W_DW;
+        uint32_t *sW = smem + buf * KS * C::W_DW;
 #pragma unroll
         for (int i = 0; i < C::W_LOADS; ++i) {
             const int p = tid + i * C::THREADS;
             if (C::W_PIECES % C::THREADS == 0 || p < C::W_PIECES) {
                 // each chunk's words w0..w7 are stored as [w0 w1 w4 w5 | w2 w3 w6 w7] so that lane
                 // half h finds the words of its steps 0..3 in one 16-byte read at 4 h
-                uint32_t *row = sW + (p >> 2) * WD_PITCH + 8 * ((p >> 1) & 1);
+                uint32_t *row = sW + (p >> 2) * WD_PITCH + 8 * ((p >> 1) & 1);  // (p>>2) = group * BN + row
                 const int half = p & 1;
                 *(uint2 *)(row + 2 * half) = make_uint2(pw[i].x, pw[i].y);
                 *(uint2 *)(row + 4 + 2 * half) = make_uint2(pw[i].z, pw[i].w);
@@ -239,23 +253,26 @@ void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, int ti
     uint4 ring[D][WM];
     fetch_w(0);
 #pragma unroll
-    for (int s = 0; s < D; ++s) load_a(ring[s], s);
+    for (int s = 0; s < D; ++s) load_a(ring[s], 8 * (kg + KS * (s / 8)) + (s & 7));
     stage_w(0);
     __syncthreads();
 
     int buf = 0;
-    for (int pr = 0; pr < npairs; ++pr) {
-        const uint32_t *sW = smem + buf * C::W_DW;
-        fetch_w(pr + 1 < npairs ? pr + 1 : pr);  // issued first: staging only waits for these
+    auto iteration = [&](int it, auto ring_half) {
+        constexpr int RH = decltype(ring_half)::value;  // which half of a 16-deep ring this slab uses
+        const int pr = it * KS + kg;  // this group's slab
+        const uint32_t *sW = smem + (buf * KS + kg) * C::W_DW;
+        fetch_w(it + 1 < niter ? it + 1 : it);  // issued first: staging only waits for these
         uint4 xw[2][WN];
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
             for (int j = 0; j < WN; ++j)
                 xw[sub][j] = *(const uint4 *)(sW + ((wn * WN + j) * 32 + r32) * WD_PITCH + 8 * sub + 4 * h);
+        if (KS == 1 || pr < npairs) {
 #pragma unroll
         for (int s8 = 0; s8 < 8; ++s8) {
-            const int slot = s8 % D, sub = s8 >> 2, s = s8 & 3;
+            const int slot = (8 * RH + s8) % D, sub = s8 >> 2, s = s8 & 3;
             v8i a[WM], b[WN];
 #pragma unroll
             for (int i = 0; i < WM; ++i) {
@@ -273,17 +290,49 @@ void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, int ti
 #pragma unroll
                 for (int i = 0; i < WM; ++i)
                     acc[j][i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b[j], a[i], acc[j][i], 4, 4, 0, 0, 0, 0);
-            load_a(ring[slot], 8 * pr + s8 + D);  // refill the slot D steps ahead
+            load_a(ring[slot], 8 * (pr + KS * (D / 8)) + s8);  // refill the slot D steps of this group ahead
+        }
         }
         stage_w(buf ^ 1);
         __syncthreads();
         buf ^= 1;
+    };
+    for (int it = 0; it < niter; it += D / 8) {
+        iteration(it, std::integral_constant<int, 0>{});
+        if (D == 16 && it + 1 < niter) iteration(it + 1, std::integral_constant<int, 1>{});
     }
 
-    // ---- epilogue.  Lane (r32, h) of block (j, i) holds token m = 32 i + r32 and channels
-    // n = 32 j + 8 g + 4 h + q (register v = 4 g + q).
+    // ---- sum the k groups' partial accumulators into group 0 (one group at a time through LDS)
+    if (KS > 1) {
+        float *red = (float *)smem;  // [wavefront in group][register][lane]; the weight slabs are dead
+        for (int r = 1; r < KS; ++r) {
+            if (kg == r) {
+#pragma unroll
+                for (int j = 0; j < WN; ++j)
+#pragma unroll
+                    for (int i = 0; i < WM; ++i)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v)
+                            red[((wl * WN * WM + j * WM + i) * 16 + v) * 64 + lane] = acc[j][i][v];
+            }
+            __syncthreads();
+            if (kg == 0) {
+#pragma unroll
+                for (int j = 0; j < WN; ++j)
+#pragma unroll
+                    for (int i = 0; i < WM; ++i)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v)
+                            acc[j][i][v] += red[((wl * WN * WM + j * WM + i) * 16 + v) * 64 + lane];
+            }
+            __syncthreads();
+        }
+    }
+
+    // ---- epilogue (k group 0 only).  Lane (r32, h) of block (j, i) holds token m = 32 i + r32 and
+    // channels n = 32 j + 8 g + 4 h + q (register v = 4 g + q).
     const int m_wave = m0 + wm * WM * 32, n_wave = n0 + wn * WN * 32;
-    if (WITH_ACC && g.acc) {
+    if (WITH_ACC && g.acc && kg == 0) {
 #pragma unroll
         for (int i = 0; i < WM; ++i) {
             const int m = m_wave + 32 * i + r32;
@@ -299,10 +348,11 @@ void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, int ti
     if (!g.out) return;
 
     float *sw_lds = (float *)smem;  // the loop's last barrier retired every read of the weight tiles
-    uint16_t *strip = (uint16_t *)(smem + C::BN) + wave * C::STRIP_HALFS;
+    uint16_t *strip = (uint16_t *)(smem + C::BN) + wl * C::STRIP_HALFS;
     constexpr int PITCH = 32 * WN + 8;  // halfs; 16-byte aligned rows, conflict-free 8-byte writes
     for (int t = tid; t < C::BN; t += C::THREADS) sw_lds[t] = (n0 + t < g.N) ? load_scale(g.s_w, n0 + t) : 0.0f;
     __syncthreads();
+    if (kg != 0) return;  // no barrier below this point
     const bool full = (m_wave + 32 * WM <= g.M) && (n_wave + 32 * WN <= g.N) && ((g.ldo & 7) == 0) &&
                       (((uintptr_t)g.out & 15) == 0);
     constexpr int LPR = 4 * WN, RPI = 64 / LPR;  // lanes per token row (8 halfs each), rows per store
@@ -346,13 +396,13 @@ void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, int ti
     }
 }
 
-template <int WM, int WN, int WAVES_M, int WAVES_N, int OCC, bool WITH_ACC>
+template <int WM, int WN, int WAVES_M, int WAVES_N, int OCC, bool WITH_ACC, int KS = 1, int D = 8>
 hipError_t launch(const GemmArgs &g, const uint32_t *frag, int s_pad, hipStream_t st)
 {
-    using C = Cfg<WM, WN, WAVES_M, WAVES_N>;
+    using C = Cfg<WM, WN, WAVES_M, WAVES_N, KS>;
     static bool configured = false;  // benign race: setting the attribute twice is harmless
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_gemm_fp4<WM, WN, WAVES_M, WAVES_N, OCC, WITH_ACC>,
+        hipError_t e = hipFuncSetAttribute((const void *)k_gemm_fp4<WM, WN, WAVES_M, WAVES_N, OCC, WITH_ACC, KS, D>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM_BYTES);
         if (e != hipSuccess) return e;
         configured = true;
@@ -360,7 +410,7 @@ hipError_t launch(const GemmArgs &g, const uint32_t *frag, int s_pad, hipStream_
     const int tiles_n = (g.N + C::BN - 1) / C::BN, tiles_m = (g.M + C::BM - 1) / C::BM;
     const int64_t total = (int64_t)tiles_n * tiles_m;
     if (total > 0x7fffffff) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((k_gemm_fp4<WM, WN, WAVES_M, WAVES_N, OCC, WITH_ACC>), dim3((unsigned)total), dim3(C::THREADS),
+    hipLaunchKernelGGL((k_gemm_fp4<WM, WN, WAVES_M, WAVES_N, OCC, WITH_ACC, KS, D>), dim3((unsigned)total), dim3(C::THREADS),
                        C::SMEM_BYTES, st, g, frag, s_pad, tiles_n, (int)total);
     return hipGetLastError();
 }
@@ -410,6 +460,11 @@ hipError_t launch_gemm_fp4(const GemmArgs &g, uint32_t *frag, bool frag_ready, h
     case 21: return launch<2, 1, 2, 2, 3, false>(g, frag, s_pad, st);
     case 12: return launch<1, 2, 2, 2, 3, false>(g, frag, s_pad, st);
     case 11: return launch<1, 1, 2, 2, 4, false>(g, frag, s_pad, st);
+    case 2216: return launch<2, 2, 2, 2, 2, false, 1, 16>(g, frag, s_pad, st);
+    case 22216: return launch<2, 2, 2, 2, 2, false, 2, 16>(g, frag, s_pad, st);
+    case 222: return launch<2, 2, 2, 2, 2, false, 2>(g, frag, s_pad, st);
+    case 322: return launch<2, 2, 2, 2, 3, false, 3>(g, frag, s_pad, st);
+    case 422: return launch<2, 2, 2, 2, 2, false, 4>(g, frag, s_pad, st);
     default: break;
     }
     // measured: long K runs best with 2 wavefronts per SIMD (179 registers), short K with 3
