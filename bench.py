@@ -27,6 +27,7 @@ if ROOT not in sys.path:
 PEAK_INT8_TOPS = 5000.0   # MI355X dense int8 MFMA, TOP/s
 PEAK_FP4_TOPS = 10100.0   # MI355X dense fp4 MFMA, TFLOP/s (the dtype the dominant kernel contracts in)
 PEAK_HBM_GBS = 8000.0     # MI355X HBM3E, GB/s
+TRAFFIC_C2_GEMM_BYTES = 22.4e6  # measured, see profiles/traffic_c2_ffn.md
 PEAK_VALU_POPC_TOPS = 1258.0  # 256 CU * 64 lanes * 2.4 GHz * 32 MAC per 2 VALU ops * 2 ops/MAC
 
 
@@ -195,7 +196,10 @@ def run_c2(args, torch, B, synth):
     roofline = {"bound": "mfma", "kernel": "k_gemm_fp4 (FP4 MFMA product + scale epilogue), mean of the two layers",
                 "achieved": round(achieved, 2), "peak": PEAK_FP4_TOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_FP4_TOPS, 4), "frac_of_int8_peak": round(achieved / PEAK_INT8_TOPS, 4),
-                "traffic": None}
+                # HBM/fabric bytes per launch (mean of the two layers) from rocprofv3 --pmc FETCH_SIZE and
+                # WRITE_SIZE runs scaled by the copy probe (profiles/traffic_c2_ffn.md): algorithmic bytes
+                # are 20.4e6 (fragments + weight bits + scales in, fp16 out), i.e. nothing is re-read
+                "traffic": TRAFFIC_C2_GEMM_BYTES}
     out = {"metric": "BWTA linear effective TOPS (ternarize+pack+GEMM+epilogue), encoder FFN shapes",
            "value": round(value, 3), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
@@ -291,12 +295,26 @@ def run_c1(args, torch, B, synth):
             "config": {"workload": "c1_tiny: M=64, N=768, K=768"}, "kernels": res}
 
 
+def run_copy_probe(args, torch, B, synth):
+    """A plain device-to-device copy of known size (256 MiB), used to calibrate the FETCH_SIZE /
+    WRITE_SIZE counters that the traffic figures in profiles/ are scaled by."""
+    n = 256 << 20
+    src = torch.ones(n, dtype=torch.uint8, device="cuda:0")
+    dst = torch.empty_like(src)
+    ms = _event_ms(torch, lambda: dst.copy_(src), max(3, args.steps // 20), 2)
+    gbs = 2 * n / (ms * 1e-3) / 1e9
+    return {"metric": "device copy bandwidth (counter calibration probe)", "value": round(gbs, 1), "unit": "GB/s",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 5),
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+            "config": {"workload": "copy_probe: 256 MiB read + 256 MiB written per launch"}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c2_ffn", choices=["c2_ffn", "c1_tiny", "c3_prefill", "c4_decode"])
+    ap.add_argument("--workload", default="c2_ffn", choices=["c2_ffn", "c1_tiny", "c3_prefill", "c4_decode", "copy_probe"])
     ap.add_argument("--decode-matrices", type=int, default=64)
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--graph", action="store_true",
@@ -314,7 +332,8 @@ def main():
     from paper_2604_03957_amd import binding as B
     from paper_2604_03957_amd import synth
     torch.cuda.set_device(0)
-    run = {"c2_ffn": run_c2, "c1_tiny": run_c1, "c3_prefill": run_c3, "c4_decode": run_c4}[args.workload]
+    run = {"c2_ffn": run_c2, "c1_tiny": run_c1, "c3_prefill": run_c3, "c4_decode": run_c4,
+           "copy_probe": run_copy_probe}[args.workload]
     out = run(args, torch, B, synth)
     print(json.dumps(out), flush=True)
 

@@ -177,14 +177,22 @@ void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, int ti
     extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
 
     // Workgroup ids are dealt round-robin to the 8 XCDs; give every XCD a contiguous range of
-    // tiles (whole strips of tokens) so that its L2 keeps re-serving the same activation rows.
-    int tile_id;
+    // tile numbers, and number the tiles in groups of 4 token strips (strip fastest) so that the
+    // tiles an XCD works on at one time share both their activation strips and their weight
+    // tile in its L2.
+    int tm, tn;
     {
         const int L = blockIdx.x, xcd = L & 7, k = L >> 3;
         const int chunk = tiles_total >> 3, rem = tiles_total & 7;
-        tile_id = xcd * chunk + (xcd < rem ? xcd : rem) + k;
+        const int id = xcd * chunk + (xcd < rem ? xcd : rem) + k;
+        const int tiles_m = tiles_total / tiles_n;
+        const int per_group = 4 * tiles_n;
+        const int grp = id / per_group, in_grp = id - grp * per_group;
+        const int first_m = 4 * grp;
+        const int gsz = tiles_m - first_m < 4 ? tiles_m - first_m : 4;
+        tm = first_m + in_grp % gsz;
+        tn = in_grp / gsz;
     }
-    const int tm = tile_id / tiles_n, tn = tile_id - tm * tiles_n;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int kg = KS == 1 ? 0 : wave / C::GROUP_WAVES;  // k group
