@@ -10,7 +10,7 @@ layers.  Inputs are resident in HBM before the timed region; weights are packed 
 Prints ONE JSON line.  `value` is effective TOPS = 2*M*N*K summed over the step / time
 (zeros counted, dense-equivalent work).  `roofline` is for the dominant kernel, timed live
 with HIP events on the launch stream; `cpu_baseline` is the CPU oracle timed on the host
-cores of the same box.  Other workloads: --workload c1_tiny | c3_prefill | c4_decode.
+cores of the same box.  Other workloads: --workload c1_tiny | c3_prefill | c4_decode | c5_block | copy_probe.
 """
 import argparse
 import json
@@ -295,6 +295,103 @@ def run_c1(args, torch, B, synth):
             "config": {"workload": "c1_tiny: M=64, N=768, K=768"}, "kernels": res}
 
 
+class Block:
+    """One 7B-style decoder block: the seven linears are BWTA layers (ternarise on the fly, one
+    ternarisation shared by Q/K/V and by gate/up), norms, attention, SiLU and the per-token scale
+    statistic are plain torch fp16 ops (the paper keeps nonlinearities in high precision)."""
+
+    def __init__(self, cfg, torch, B):
+        self.torch, self.B = torch, B
+        self.S, self.H, self.F, self.heads = cfg["seq"], cfg["hidden"], cfg["ffn"], cfg["heads"]
+        dev = "cuda:0"
+        self.x = _dev(cfg["x"], torch)
+        self.w, self.sw = {}, {}
+        for nm, K, N in [("wq", self.H, self.H), ("wk", self.H, self.H), ("wv", self.H, self.H), ("wo", self.H, self.H),
+                         ("wgate", self.H, self.F), ("wup", self.H, self.F), ("wdown", self.F, self.H)]:
+            wd = _dev(cfg[nm], torch)
+            ws = torch.empty((N, B.plane_row_words(K)), dtype=torch.int32, device=dev)
+            B.bwta_pack_weights(wd, ws, N=N, K=K)
+            self.w[nm], self.sw[nm] = ws, _dev(cfg["s_" + nm], torch)
+            del wd
+        S, H, F = self.S, self.H, self.F
+        self.prep_h = torch.empty(B.prepared_bytes(S, H), dtype=torch.uint8, device=dev)
+        self.prep_f = torch.empty(B.prepared_bytes(S, F), dtype=torch.uint8, device=dev)
+        self.q, self.k, self.v, self.o = (torch.empty((S, H), dtype=torch.float16, device=dev) for _ in range(4))
+        self.g, self.u = (torch.empty((S, F), dtype=torch.float16, device=dev) for _ in range(2))
+        self.d = torch.empty((S, H), dtype=torch.float16, device=dev)
+        torch.cuda.synchronize()
+
+    def _norm(self, x):
+        xf = x.float()
+        return (xf * self.torch.rsqrt(xf.pow(2).mean(-1, keepdim=True) + 1e-6)).half()
+
+    def _scale(self, a):  # the value the activation scale is initialised with, per token
+        return (2.0 * a.float().abs().mean(dim=1)).half()
+
+    def _lin(self, prep, s_a, nm, out, K, N):
+        self.B.bwta_gemm_prepared(prep, self.w[nm], s_a, self.sw[nm], None, out, M=self.S, N=N, K=K)
+
+    def forward(self, bwta_only=False):
+        """bwta_only: run just the 4 ternarisations and 7 products on whatever the buffers hold."""
+        torch, B, S, H, F = self.torch, self.B, self.S, self.H, self.F
+        h = self.x if bwta_only else self._norm(self.x)
+        s = self.s1 if bwta_only else self._scale(h)
+        B.bwta_prepare_act(h, s, self.prep_h, M=S, K=H)
+        for nm, out in (("wq", self.q), ("wk", self.k), ("wv", self.v)):
+            self._lin(self.prep_h, s, nm, out, H, H)
+        if bwta_only:
+            att, s2 = self.att, self.s2
+        else:
+            hd = H // self.heads
+            q, k, v = (t.view(S, self.heads, hd).transpose(0, 1).unsqueeze(0) for t in (self.q, self.k, self.v))
+            att = torch.nn.functional.scaled_dot_product_attention(q, k, v, is_causal=True)
+            att = att.squeeze(0).transpose(0, 1).reshape(S, H).contiguous()
+            s2 = self._scale(att)
+        B.bwta_prepare_act(att, s2, self.prep_h, M=S, K=H)
+        self._lin(self.prep_h, s2, "wo", self.o, H, H)
+        if bwta_only:
+            h2, s3 = self.h2, self.s3
+        else:
+            x1 = self.x + self.o
+            h2 = self._norm(x1)
+            s3 = self._scale(h2)
+        B.bwta_prepare_act(h2, s3, self.prep_h, M=S, K=H)
+        self._lin(self.prep_h, s3, "wgate", self.g, H, F)
+        self._lin(self.prep_h, s3, "wup", self.u, H, F)
+        if bwta_only:
+            act, s4 = self.act, self.s4
+        else:
+            act = torch.nn.functional.silu(self.g) * self.u
+            s4 = self._scale(act)
+        B.bwta_prepare_act(act, s4, self.prep_f, M=S, K=F)
+        self._lin(self.prep_f, s4, "wdown", self.d, F, H)
+        if bwta_only:
+            return None
+        self.s1, self.att, self.s2, self.h2, self.s3, self.act, self.s4 = s, att, s2, h2, s3, act, s4
+        return x1 + self.d
+
+
+def run_c5(args, torch, B, synth):
+    blk = Block(synth.config5(), torch, B)
+    y = blk.forward()
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(y).all()), "block output is not finite"
+    steps = max(5, args.steps // 10)
+    ms_block = _event_ms(torch, blk.forward, steps, 3)
+    ms_bwta = _event_ms(torch, lambda: blk.forward(bwta_only=True), steps, 3)
+    S, H, F = blk.S, blk.H, blk.F
+    ops = 2.0 * S * (4 * H * H + 3 * H * F)
+    return {"metric": "BWTA decoder block latency (7 BWTA linears + fp16 attention/norms)", "value": round(ms_block * 1e3, 1),
+            "unit": "us", "n_gpus": 1, "steps": steps, "warmup": 3, "ms_per_step": round(ms_block, 5),
+            "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "fp4 (E2M1 operands, exact)",
+            "data": "synthetic",
+            "config": {"workload": "c5_block: hidden 4096, FFN 11008, 32 heads, seq 2048, batch 1; Laplace(0,1) input"},
+            "kernels": {"bwta_part_us": round(ms_bwta * 1e3, 1), "bwta_share": round(ms_bwta / ms_block, 3),
+                        "bwta_effective_TOPS": round(ops / (ms_bwta * 1e-3) / 1e12, 1),
+                        "note": "bwta part = 4 ternarisations + 7 products; the rest is torch fp16 attention, "
+                                "RMSNorm, SiLU, residuals and the per-token scale statistic"}}
+
+
 def run_copy_probe(args, torch, B, synth):
     """A plain device-to-device copy of known size (256 MiB), used to calibrate the FETCH_SIZE /
     WRITE_SIZE counters that the traffic figures in profiles/ are scaled by."""
@@ -314,7 +411,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c2_ffn", choices=["c2_ffn", "c1_tiny", "c3_prefill", "c4_decode", "copy_probe"])
+    ap.add_argument("--workload", default="c2_ffn", choices=["c2_ffn", "c1_tiny", "c3_prefill", "c4_decode", "c5_block", "copy_probe"])
     ap.add_argument("--decode-matrices", type=int, default=64)
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--graph", action="store_true",
@@ -333,7 +430,7 @@ def main():
     from paper_2604_03957_amd import synth
     torch.cuda.set_device(0)
     run = {"c2_ffn": run_c2, "c1_tiny": run_c1, "c3_prefill": run_c3, "c4_decode": run_c4,
-           "copy_probe": run_copy_probe}[args.workload]
+           "c5_block": run_c5, "copy_probe": run_copy_probe}[args.workload]
     out = run(args, torch, B, synth)
     print(json.dumps(out), flush=True)
 

@@ -155,7 +155,9 @@ BLOCK_LINEARS = [("wq", 4096, 4096), ("wk", 4096, 4096), ("wv", 4096, 4096), ("w
 
 
 def config5(seq=2048, hidden=4096, ffn=11008):
-    """One decoder block: Laplace hidden states and the seven +-1 weight matrices."""
+    """One decoder block: Laplace hidden states and the seven +-1 weight matrices.  Channel scales
+    are U(0.5, 1.5) / sqrt(K), the size mean|W| has in a trained layer of fan-in K, so that the
+    block's fp16 intermediates stay in range."""
     seed = 4
     out = dict(name="c5_block", seq=seq, hidden=hidden, ffn=ffn, heads=32,
                x=laplace_activations(seed, 1, seq, hidden))
@@ -165,5 +167,5 @@ def config5(seq=2048, hidden=4096, ffn=11008):
     for i, (nm, _, _) in enumerate(BLOCK_LINEARS):
         K, N = dims[nm]
         out[nm] = binary_pm1(seed, 10 + 2 * i, (N, K))
-        out["s_" + nm] = scales(seed, 11 + 2 * i, N)
+        out["s_" + nm] = scales(seed, 11 + 2 * i, N, lo=0.5 / np.sqrt(K), hi=1.5 / np.sqrt(K))
     return out

@@ -83,3 +83,35 @@ def test_config4_decode_gemm_full(which, M):
     want_acc = oracle.gemm_unpacked(c["t"], c["w"])
     assert np.array_equal(acc.cpu().numpy(), want_acc)
     assert same_half(out.cpu().numpy(), oracle.epilogue(want_acc, c["s_a"], c["s_w"]))
+
+
+@pytest.mark.parametrize("name,K,N", [("wq", 4096, 4096), ("wgate", 4096, 11008), ("wdown", 11008, 4096)])
+def test_config5_block_linears_sampled_rows(name, K, N):
+    """The block's linears at full size on Laplace(0,1) inputs, ternarised on the fly; one
+    ternarisation feeds the product (prepare + gemm_prepared, as the block harness calls them)."""
+    seed, M = 4, 2048
+    print("config5", name, M, N, K, flush=True)
+    x = synth.laplace_activations(seed, 100 + K % 97, M, K)
+    s_a = synth.token_scales_l1(x)
+    w = synth.binary_pm1(seed, 200 + N % 89, (N, K))
+    s_w = synth.scales(seed, 300, N)
+    prep = torch.empty(B.prepared_bytes(M, K), dtype=torch.uint8, device="cuda:0")
+    out = torch.empty((M, N), dtype=torch.float16, device="cuda:0")
+    dsa = dev(s_a)
+    B.bwta_prepare_act(dev(x), dsa, prep, M=M, K=K)
+    B.bwta_gemm_prepared(prep, gpu_pack_weights(w), dsa, dev(s_w), None, out, M=M, N=N, K=K)
+    torch.cuda.synchronize()
+    rows = _rows(M, 5)
+    t, _, want = oracle.linear(x[rows], s_a[rows], w, s_w)
+    assert same_half(np.ascontiguousarray(out.cpu().numpy()[rows]), want)
+    zero_frac = float(np.mean(t == 0))
+    assert abs(zero_frac - (1 - np.exp(-1))) < 0.02      # Laplace with scale 2 E|x|: 1 - 1/e zeros
+
+
+def test_config5_block_runs_and_is_finite():
+    import bench
+    blk = bench.Block(synth.config5(seq=256), torch, B)
+    y = blk.forward()
+    blk.forward(bwta_only=True)
+    torch.cuda.synchronize()
+    assert y.shape == (256, 4096) and bool(torch.isfinite(y).all())
