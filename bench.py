@@ -263,15 +263,21 @@ def run_c4(args, torch, B, synth):
             ms = _event_ms(torch, grouped, max(3, args.steps // 4), 2) / nmat
             single = _event_ms(torch, lambda: L.gemm(B), args.steps, args.warmup)
             gbs = L.gemm_bytes() / (ms * 1e-3) / 1e9
+            fam = {}
+            for name, path in (("popc", B.PATH_POPC), ("fp4", B.PATH_FP4)):  # both decode kernel families
+                B.set_path(path)
+                fam[name + "_us"] = round(_event_ms(torch, grouped, max(3, args.steps // 4), 2) / nmat * 1e3, 3)
+            B.set_path(B.PATH_AUTO)
             res.append(dict(layer=c["name"], M=M, N=L.N, K=L.K, us_per_matrix=round(ms * 1e3, 3), GBs=round(gbs, 1),
                             frac_hbm=round(gbs / PEAK_HBM_GBS, 4), single_launch_us=round(single * 1e3, 2),
-                            path=_kernel_path_name(B, L.M, L.N, L.K)))
+                            path=_kernel_path_name(B, L.M, L.N, L.K), **fam))
             del mats, outs, ws, L
     mean = float(np.mean([r["GBs"] for r in res]))
     return {"metric": "BWTA decode GEMM achieved HBM GB/s (weights streamed once)", "value": round(mean, 1),
             "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
             "ms_per_step": round(float(np.mean([r["us_per_matrix"] for r in res])) / 1e3, 6),
-            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32 (popcount)",
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "fp4 (E2M1 operands, exact) above 2 tokens, int32 popcount below",
             "data": "synthetic",
             "config": {"workload": "c4_decode: M in {1,4,16}, (K,N) in {(4096,11008),(11008,4096)}, %d distinct "
                                    "weight matrices per timed region (bwta_gemm_grouped)" % nmat},

@@ -31,10 +31,23 @@ int resolve_path(int M, int N, int K)
     return p == BWTA_PATH_AUTO ? bwta_auto_path(M, N, K) : p;  // AUTO depends on M only
 }
 
+// the FP4 path consumes activation fragments (prefill kernel) unless the shape is decode-sized, in
+// which case the matrix-core decode kernel reads the canonical planes directly
+bool fp4_uses_fragments(int M, int K)
+{
+    bwta::GemmArgs g{};
+    g.M = M;
+    g.N = 1;
+    g.K = K;
+    g.rw = (int)(4 * (((int64_t)K + 127) / 128));
+    return resolve_path(M, 1, K) == BWTA_PATH_FP4 && !bwta::gemv_fp4_supported(g);
+}
+
 // workspace layout: [mask planes | sign planes | FP4 activation fragments]
 int run_gemm(const bwta::GemmArgs &g, void *workspace, hipStream_t st)
 {
     int path = resolve_path(g.M, g.N, g.K);
+    if (path == BWTA_PATH_FP4 && bwta::gemv_fp4_supported(g)) return hip_result(bwta::launch_gemv_fp4(g, st));
     if (path == BWTA_PATH_FP4) {
         uint32_t *frag = (uint32_t *)((char *)workspace + 2 * plane_bytes(g.M, g.K));
         return hip_result(bwta::launch_gemm_fp4(g, frag, false, st));
@@ -160,7 +173,7 @@ int bwta_prepare_act(const void *A, int64_t lda, const void *s_a, int a_scale_mo
     if (!aligned(prepared, 256)) return BWTA_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
     bwta::ScaleArg sa{(const uint16_t *)s_a, s_a ? a_scale_mode : BWTA_SCALE_NONE};
-    if (resolve_path(M, 1, K) == BWTA_PATH_FP4) {
+    if (fp4_uses_fragments(M, K)) {
         uint32_t *frag = (uint32_t *)((char *)prepared + 2 * plane_bytes(M, K));
         return hip_result(bwta::launch_quantize_to_fp4(A, lda, sa, M, K, frag, st));
     }
@@ -188,7 +201,7 @@ int bwta_gemm_prepared(const void *prepared, size_t prepared_bytes, const uint32
                      {(const uint16_t *)s_a, s_a ? a_scale_mode : BWTA_SCALE_NONE},
                      {(const uint16_t *)s_w, s_w ? w_scale_mode : BWTA_SCALE_NONE},
                      acc, (uint16_t *)out, ldo};
-    if (resolve_path(M, 1, K) == BWTA_PATH_FP4) {
+    if (fp4_uses_fragments(M, K)) {
         uint32_t *frag = (uint32_t *)((char *)prepared + 2 * plane_bytes(M, K));
         return hip_result(bwta::launch_gemm_fp4(g, frag, true, st));
     }
@@ -224,12 +237,15 @@ int bwta_gemm_grouped(const bwta_gemm_problem *problems, int count, int M, int N
                               p.acc, (uint16_t *)p.out, ldo};
     };
     bwta::GemmArgs first = args_of(problems[0]);
-    if (resolve_path(M, N, K) == BWTA_PATH_POPC && bwta::gemv_popc_supported(first)) {
+    const int path = resolve_path(M, N, K);
+    const bool dec_fp4 = path == BWTA_PATH_FP4 && bwta::gemv_fp4_supported(first);
+    if (dec_fp4 || (path == BWTA_PATH_POPC && bwta::gemv_popc_supported(first))) {
         bwta::GemmArgs batch[32];
         for (int base = 0; base < count; base += 32) {
             const int n = count - base < 32 ? count - base : 32;
             for (int i = 0; i < n; ++i) batch[i] = args_of(problems[base + i]);
-            int rc = hip_result(bwta::launch_gemv_popc_grouped(batch, n, st));
+            int rc = hip_result(dec_fp4 ? bwta::launch_gemv_fp4_grouped(batch, n, st)
+                                        : bwta::launch_gemv_popc_grouped(batch, n, st));
             if (rc != BWTA_OK) return rc;
         }
         return BWTA_OK;
@@ -270,13 +286,21 @@ int bwta_auto_path(int M, int N, int K)
 {
     (void)N;
     (void)K;
-    return M > 16 ? BWTA_PATH_FP4 : BWTA_PATH_POPC;
+    // one or two tokens: the popcount decode kernel; more: the FP4 matrix cores (decode kernel up to
+    // 16 tokens, tiled kernel above)
+    return M > 2 ? BWTA_PATH_FP4 : BWTA_PATH_POPC;
 }
 
 int bwta_version(void) { return 1; }
 
 int bwta_set_tile(int tile)
 {
+    if (tile >= 2000) {  // matrix-core decode kernel: 2000 + 1024 * ring depth + 64 * chunks-per-wavefront + tiles-per-workgroup
+        const int c = tile - 2000;
+        bwta::set_gemv_fp4_tile((c / 64) % 16, c % 64, c / 1024);
+        return BWTA_OK;
+    }
+    bwta::set_gemv_fp4_tile(0, 0, 0);
     if (tile >= 1000) {  // decode kernel: 1000 + 16 * lanes-per-row + chunks-per-lane
         bwta::set_gemv_tile((tile - 1000) / 16, (tile - 1000) % 16);
         return BWTA_OK;

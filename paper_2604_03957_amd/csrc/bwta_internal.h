@@ -29,6 +29,10 @@ hipError_t launch_gemm_popc(const GemmArgs &g, hipStream_t st);
 bool gemv_popc_supported(const GemmArgs &g);
 hipError_t launch_gemv_popc(const GemmArgs &g, hipStream_t st);
 hipError_t launch_gemv_popc_grouped(const GemmArgs *gs, int count, hipStream_t st);
+bool gemv_fp4_supported(const GemmArgs &g);
+hipError_t launch_gemv_fp4(const GemmArgs &g, hipStream_t st);
+hipError_t launch_gemv_fp4_grouped(const GemmArgs *gs, int count, hipStream_t st);
+void set_gemv_fp4_tile(int rpw, int t, int pf);
 bool gemm_mfma_supported(const GemmArgs &g);
 hipError_t launch_gemm_mfma(const GemmArgs &g, hipStream_t st);
 

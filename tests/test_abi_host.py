@@ -41,7 +41,7 @@ def test_path_selection():
     with pytest.raises(B.BwtaError) as e:
         B.set_path(7)
     assert e.value.code == B.ERR_UNSUPPORTED
-    assert B.auto_path(1, 11008, 4096) == B.PATH_POPC and B.auto_path(16, 11008, 4096) == B.PATH_POPC
+    assert B.auto_path(1, 11008, 4096) == B.PATH_POPC and B.auto_path(16, 11008, 4096) == B.PATH_FP4
     assert B.auto_path(2048, 4096, 4096) in (B.PATH_MFMA, B.PATH_FP4)
 
 

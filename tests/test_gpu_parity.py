@@ -153,7 +153,8 @@ def test_gemm_matches_oracle(M, N, K, path):
 
 DECODE_SHAPES = [(1, 7, 33), (2, 130, 128), (3, 257, 1000), (1, 1001, 4096), (4, 999, 4096), (8, 300, 4096),
                  (5, 258, 8192), (1, 515, 11008), (4, 130, 11008), (8, 67, 11008), (2, 70, 16384),
-                 (3, 40, 16512), (9, 100, 4096), (13, 77, 1408), (16, 257, 11008), (16, 90, 768)]
+                 (3, 40, 16512), (9, 100, 4096), (13, 77, 1408), (16, 257, 11008), (16, 90, 768),
+                 (16, 40, 17000), (7, 33, 30000), (12, 16, 512), (15, 17, 513)]
 
 
 @pytest.mark.parametrize("M,N,K", DECODE_SHAPES)
@@ -162,6 +163,25 @@ def test_decode_shaped_gemm_matches_oracle(M, N, K):
     t, w, s_a, s_w = _gemm_case(2000 + M + N, M, N, K, p0=0.5)
     assert _check_gemm(t, w, s_a, s_w, B.PATH_AUTO)
     assert _check_gemm(t, w, s_a, s_w, B.PATH_POPC, dirty_sign=True)
+    assert _check_gemm(t, w, s_a, s_w, B.PATH_FP4, dirty_sign=True)
+
+
+@pytest.mark.parametrize("rpw,tiles,pf", [(1, 2, 2), (1, 8, 2), (1, 8, 4), (2, 2, 2), (2, 4, 2), (2, 8, 2), (2, 8, 4),
+                                          (2, 16, 4), (3, 2, 2), (3, 4, 2), (3, 8, 2), (3, 8, 4), (4, 2, 2), (4, 4, 2),
+                                          (4, 8, 2), (4, 8, 4)])
+def test_matrix_core_decode_every_work_split(rpw, tiles, pf):
+    """Chunks per wavefront x channel tiles per workgroup x ring depth of the matrix-core decode
+    kernel, on shapes with ragged N, a K tail inside a chunk, and more tiles than one workgroup takes."""
+    _say("decode fp4 split", rpw, tiles, pf)
+    B.set_tile(2000 + 1024 * pf + 64 * rpw + tiles)
+    try:
+        for M, N, K in [(16, 100, 4096), (11, 70, 11008), (1, 33, 200), (5, 1000, 1000)]:
+            if -(-B.plane_row_words(K) // 16) > 16 * rpw:
+                continue
+            t, w, s_a, s_w = _gemm_case(2500 + M + rpw, M, N, K, p0=0.5)
+            assert _check_gemm(t, w, s_a, s_w, B.PATH_FP4)
+    finally:
+        B.set_tile(0)
 
 
 @pytest.mark.parametrize("path", PATHS)
@@ -291,9 +311,10 @@ def test_prepare_once_feed_several_weight_matrices(path):
         B.set_path(B.PATH_AUTO)
 
 
+@pytest.mark.parametrize("path", [B.PATH_AUTO, B.PATH_POPC, B.PATH_FP4])
 @pytest.mark.parametrize("M,N,K,count", [(1, 300, 4096, 3), (4, 130, 11008, 2), (8, 70, 1000, 35), (16, 64, 512, 2)])
-def test_gemm_grouped_matches_oracle(M, N, K, count):
-    _say("grouped", M, N, K, count)
+def test_gemm_grouped_matches_oracle(M, N, K, count, path):
+    _say("grouped", M, N, K, count, path)
     t, _, s_a, _ = _gemm_case(3000 + M, M, N, K, p0=0.5)
     mask, sign, _ = oracle.pack_act(t)
     dm, dsg, dsa = dev(mask), dev(sign), dev(s_a)
@@ -309,8 +330,12 @@ def test_gemm_grouped_matches_oracle(M, N, K, count):
         keep.append((dw, dsw, acc, out))
         probs.append((dm, dsg, dw, dsa, dsw, acc, out))
     ws = torch.empty(max(B.workspace_bytes(M, N, K), 256) * count, dtype=torch.uint8, device="cuda:0")
-    B.bwta_gemm_grouped(B.make_problems(probs), ws, M=M, N=N, K=K)
-    torch.cuda.synchronize()
+    B.set_path(path)
+    try:
+        B.bwta_gemm_grouped(B.make_problems(probs), ws, M=M, N=N, K=K)
+        torch.cuda.synchronize()
+    finally:
+        B.set_path(B.PATH_AUTO)
     for (dw, dsw, acc, out), (acc_want, out_want) in zip(keep, want):
         assert np.array_equal(acc.cpu().numpy(), acc_want)
         assert same_half(out.cpu().numpy(), out_want)
