@@ -244,7 +244,7 @@ def run_c3(args, torch, B, synth):
 
 def run_c4(args, torch, B, synth):
     """Decode: stream `nmat` distinct packed weight matrices (> Infinity Cache) per timed region
-    through one grouped call (one kernel launch per 32 matrices), plus the latency of one matrix."""
+    through one grouped call (one kernel launch per 64 matrices), plus the latency of one matrix."""
     nmat = args.decode_matrices
     res = []
     for which in ("upgate", "down"):
@@ -260,13 +260,13 @@ def run_c4(args, torch, B, synth):
             def grouped():
                 B.bwta_gemm_grouped(probs, ws, M=L.M, N=L.N, K=L.K)
 
-            ms = _event_ms(torch, grouped, max(3, args.steps // 4), 2) / nmat
+            ms = _event_ms(torch, grouped, max(5, args.steps // 2), 3) / nmat
             single = _event_ms(torch, lambda: L.gemm(B), args.steps, args.warmup)
             gbs = L.gemm_bytes() / (ms * 1e-3) / 1e9
             fam = {}
             for name, path in (("popc", B.PATH_POPC), ("fp4", B.PATH_FP4)):  # both decode kernel families
                 B.set_path(path)
-                fam[name + "_us"] = round(_event_ms(torch, grouped, max(3, args.steps // 4), 2) / nmat * 1e3, 3)
+                fam[name + "_us"] = round(_event_ms(torch, grouped, max(5, args.steps // 2), 3) / nmat * 1e3, 3)
             B.set_path(B.PATH_AUTO)
             res.append(dict(layer=c["name"], M=M, N=L.N, K=L.K, us_per_matrix=round(ms * 1e3, 3), GBs=round(gbs, 1),
                             frac_hbm=round(gbs / PEAK_HBM_GBS, 4), single_launch_us=round(single * 1e3, 2),

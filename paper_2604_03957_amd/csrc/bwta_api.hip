@@ -240,9 +240,9 @@ int bwta_gemm_grouped(const bwta_gemm_problem *problems, int count, int M, int N
     const int path = resolve_path(M, N, K);
     const bool dec_fp4 = path == BWTA_PATH_FP4 && bwta::gemv_fp4_supported(first);
     if (dec_fp4 || (path == BWTA_PATH_POPC && bwta::gemv_popc_supported(first))) {
-        bwta::GemmArgs batch[32];
-        for (int base = 0; base < count; base += 32) {
-            const int n = count - base < 32 ? count - base : 32;
+        bwta::GemmArgs batch[64];
+        for (int base = 0; base < count; base += 64) {
+            const int n = count - base < 64 ? count - base : 64;
             for (int i = 0; i < n; ++i) batch[i] = args_of(problems[base + i]);
             int rc = hip_result(dec_fp4 ? bwta::launch_gemv_fp4_grouped(batch, n, st)
                                         : bwta::launch_gemv_popc_grouped(batch, n, st));

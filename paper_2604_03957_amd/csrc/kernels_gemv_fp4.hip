@@ -36,7 +36,7 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 typedef unsigned v4u __attribute__((ext_vector_type(4)));
 
 struct DecodeBatch {
-    static constexpr int MAX = 32;
+    static constexpr int MAX = 64;
     const uint32_t *mask[MAX], *sign[MAX], *wsign[MAX];
     const uint16_t *s_a[MAX], *s_w[MAX];
     int32_t *acc[MAX];

@@ -45,7 +45,7 @@ __device__ __forceinline__ int group_sum(int v)
 }
 
 struct GemvBatch {
-    static constexpr int MAX = 32;
+    static constexpr int MAX = 64;
     const uint32_t *mask[MAX], *sign[MAX], *wsign[MAX];
     const uint16_t *s_a[MAX], *s_w[MAX];
     int32_t *acc[MAX];
