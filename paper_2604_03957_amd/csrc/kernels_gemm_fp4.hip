@@ -163,9 +163,12 @@ struct Cfg {
     static constexpr int EPI_BYTES = BN * 4 + GROUP_WAVES * STRIP_HALFS * 2;
     static constexpr int RED_BYTES = KS > 1 ? GROUP_WAVES * WM * WN * 16 * 64 * 4 : 0;
     static constexpr int LOOP_BYTES = 2 * KS * W_DW * 4;
-    static constexpr int SMEM_BYTES =
+    static constexpr int WORK_BYTES =
         (LOOP_BYTES > EPI_BYTES ? LOOP_BYTES : EPI_BYTES) > RED_BYTES ? (LOOP_BYTES > EPI_BYTES ? LOOP_BYTES : EPI_BYTES)
                                                                       : RED_BYTES;
+    static constexpr int SCALE_BYTES = (BN + BM) * 4;  // the tile's s_w and s_a as floats, fetched at the start
+    static constexpr int SMEM_BYTES = WORK_BYTES + SCALE_BYTES;
+    static_assert(BN <= THREADS && BM <= THREADS, "one thread per scale");
 };
 
 template <int WM, int WN, int WAVES_M, int WAVES_N, int OCC, bool WITH_ACC, int KS, int D>
@@ -203,6 +206,7 @@ void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, int ti
     const int rw = g.rw;
     const int npairs = s_pad / 8;  // slabs of 8 k steps (512 k); the fragment buffer is padded to that
     const int niter = (npairs + KS - 1) / KS;
+    const int nsteps = rw >> 1;  // k steps of 64 that hold data (rw is a multiple of 4 words)
 
     uint32_t m88 = 0x88888888u, c22 = 0x22222222u;
     asm volatile("" : "+s"(m88));
@@ -221,8 +225,11 @@ void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, int ti
 
     // weight words of 512 k; rows / words past the end are clamped (their products meet zero
     // activations or land in channels that are never stored)
-    uint4 pw[C::W_LOADS];
-    auto fetch_w = [&](int it) {  // slabs it*KS .. it*KS+KS-1, one per k group
+    // Weight slabs are requested WPF iterations before they are staged: one iteration of 8 k steps
+    // is shorter than a trip to memory when only one or two wavefronts share a SIMD.
+    constexpr int WPF = OCC >= 3 ? 1 : 2;
+    uint4 pwbuf[WPF][C::W_LOADS];
+    auto fetch_w = [&](int it, uint4 (&pw)[C::W_LOADS]) {  // slabs it*KS .. it*KS+KS-1, one per k group
 #pragma unroll
         for (int i = 0; i < C::W_LOADS; ++i) {
             const int p = tid + i * C::THREADS;  // piece: group p/(4 BN), row (p/4)%BN, quarter p%4
@@ -234,7 +241,7 @@ void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, int ti
                 pw[i] = *(const uint4 *)(g.wsign + (int64_t)n * rw + kw);
         }
     };
-    auto stage_w = [&](int buf) {
+    auto stage_w = [&](int buf, const uint4 (&pw)[C::W_LOADS]) {
         uint32_t *sW = smem + buf * KS * C::W_DW;
 #pragma unroll
         for (int i = 0; i < C::W_LOADS; ++i) {
@@ -258,28 +265,47 @@ void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, int ti
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[j][i][v] = 0.0f;
 
+    // The tile's scales are requested before anything else and parked in LDS with the first weight
+    // slab, so the epilogue never waits on a global load.
+    float *sc_lds = (float *)(smem + C::WORK_BYTES / 4);  // [BN] channel scales, then [BM] token scales
+    float my_sw = 0.0f, my_sa = 0.0f;
+    if (tid < C::BN && n0 + tid < g.N) my_sw = load_scale(g.s_w, n0 + tid);
+    if (tid < C::BM && m0 + tid < g.M) my_sa = load_scale(g.s_a, m0 + tid);
+
     uint4 ring[D][WM];
-    fetch_w(0);
+    fetch_w(0, pwbuf[0]);
 #pragma unroll
     for (int s = 0; s < D; ++s) load_a(ring[s], 8 * (kg + KS * (s / 8)) + (s & 7));
-    stage_w(0);
+    stage_w(0, pwbuf[0]);
+    if (WPF == 2 && niter > 1) fetch_w(1, pwbuf[WPF - 1]);  // staged at the end of iteration 0
+    if (tid < C::BN) sc_lds[tid] = my_sw;
+    if (tid < C::BM) sc_lds[C::BN + tid] = my_sa;
     __syncthreads();
 
     int buf = 0;
-    auto iteration = [&](int it, auto ring_half) {
-        constexpr int RH = decltype(ring_half)::value;  // which half of a 16-deep ring this slab uses
+    // Every path through a full iteration issues the same loads (weight slab always, clamped to the
+    // last one; ring refills always, clamped to the last step), so the wait counters the compiler
+    // derives do not collapse to the shortest path.  A last slab that holds data only in its first
+    // four steps (K = 768: 12 steps) runs as a peeled half iteration without any loads.
+    auto iteration = [&](int it, auto parity, auto half_only) {
+        constexpr int PAR = decltype(parity)::value;    // it & 1
+        constexpr bool HALF = decltype(half_only)::value;
+        constexpr int RH = D == 16 ? PAR : 0;           // which half of a 16-deep ring this slab uses
+        constexpr int PWN = WPF == 2 ? PAR : 0;         // registers that receive the slab requested now
+        constexpr int PWS = WPF == 2 ? PAR ^ 1 : 0;     // registers that hold the slab staged at the end
         const int pr = it * KS + kg;  // this group's slab
         const uint32_t *sW = smem + (buf * KS + kg) * C::W_DW;
-        fetch_w(it + 1 < niter ? it + 1 : it);  // issued first: staging only waits for these
+        const bool more = it + 1 < niter;
+        if (!HALF) fetch_w(it + WPF < niter ? it + WPF : niter - 1, pwbuf[PWN]);  // staging only waits for older loads
         uint4 xw[2][WN];
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
+        for (int sub = 0; sub < (HALF ? 1 : 2); ++sub)
 #pragma unroll
             for (int j = 0; j < WN; ++j)
                 xw[sub][j] = *(const uint4 *)(sW + ((wn * WN + j) * 32 + r32) * WD_PITCH + 8 * sub + 4 * h);
         if (KS == 1 || pr < npairs) {
 #pragma unroll
-        for (int s8 = 0; s8 < 8; ++s8) {
+        for (int s8 = 0; s8 < (HALF ? 4 : 8); ++s8) {
             const int slot = (8 * RH + s8) % D, sub = s8 >> 2, s = s8 & 3;
             v8i a[WM], b[WN];
 #pragma unroll
@@ -298,16 +324,31 @@ void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, int ti
 #pragma unroll
                 for (int i = 0; i < WM; ++i)
                     acc[j][i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b[j], a[i], acc[j][i], 4, 4, 0, 0, 0, 0);
-            load_a(ring[slot], 8 * (pr + KS * (D / 8)) + s8);  // refill the slot D steps of this group ahead
+            if (!HALF) load_a(ring[slot], 8 * (pr + KS * (D / 8)) + s8);  // refill the slot D steps of this group ahead
         }
         }
-        stage_w(buf ^ 1);
+        if (!HALF && more) stage_w(buf ^ 1, pwbuf[PWS]);  // nothing to stage after the last slab
         __syncthreads();
         buf ^= 1;
     };
-    for (int it = 0; it < niter; it += D / 8) {
-        iteration(it, std::integral_constant<int, 0>{});
-        if (D == 16 && it + 1 < niter) iteration(it + 1, std::integral_constant<int, 1>{});
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    const bool tail_half = KS == 1 && (nsteps & 7) != 0 && (nsteps & 7) <= 4;
+    const int nfull = niter - (tail_half ? 1 : 0);
+    if constexpr (WPF == 1 && D == 8) {  // nothing depends on the parity: one copy of the body
+        for (int it = 0; it < nfull; ++it) iteration(it, P0{}, std::false_type{});
+        if (tail_half) iteration(nfull, P0{}, std::true_type{});
+    } else {
+        for (int it = 0; it < nfull; it += 2) {
+            iteration(it, P0{}, std::false_type{});
+            if (it + 1 < nfull) iteration(it + 1, P1{}, std::false_type{});
+        }
+        if (tail_half) {
+            if (nfull & 1)
+                iteration(nfull, P1{}, std::true_type{});
+            else
+                iteration(nfull, P0{}, std::true_type{});
+        }
     }
 
     // ---- sum the k groups' partial accumulators into group 0 (one group at a time through LDS)
@@ -355,19 +396,17 @@ void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, int ti
     }
     if (!g.out) return;
 
-    float *sw_lds = (float *)smem;  // the loop's last barrier retired every read of the weight tiles
+    const float *sw_lds = sc_lds, *sa_lds = sc_lds + C::BN;
+    // the loop's last barrier retired every read of the weight slabs, whose LDS the strips reuse
     uint16_t *strip = (uint16_t *)(smem + C::BN) + wl * C::STRIP_HALFS;
     constexpr int PITCH = 32 * WN + 8;  // halfs; 16-byte aligned rows, conflict-free 8-byte writes
-    for (int t = tid; t < C::BN; t += C::THREADS) sw_lds[t] = (n0 + t < g.N) ? load_scale(g.s_w, n0 + t) : 0.0f;
-    __syncthreads();
     if (kg != 0) return;  // no barrier below this point
     const bool full = (m_wave + 32 * WM <= g.M) && (n_wave + 32 * WN <= g.N) && ((g.ldo & 7) == 0) &&
                       (((uintptr_t)g.out & 15) == 0);
     constexpr int LPR = 4 * WN, RPI = 64 / LPR;  // lanes per token row (8 halfs each), rows per store
 #pragma unroll
     for (int i = 0; i < WM; ++i) {
-        const int m = m_wave + 32 * i + r32;
-        const float sa = m < g.M ? load_scale(g.s_a, m) : 0.0f;
+        const float sa = sa_lds[wm * WM * 32 + 32 * i + r32];
 #pragma unroll
         for (int j = 0; j < WN; ++j) {
 #pragma unroll
