@@ -158,6 +158,38 @@ int bwta_gemm_grouped(const bwta_gemm_problem *problems, int count, int M, int N
                       size_t workspace_bytes, bwta_stream_t stream);
 
 /* Human-readable text for a return code (static storage). */
+/*
+ * Boolean activations (the paper's bool function, used for attention probabilities and other
+ * non-negative activations): bit k of word k / 32 of row m = 1 iff A[m, k] >= 0.5 * s (exact
+ * compare, no division).  A is fp16 [M, lda]; scale rules as in bwta_quantize_pack_act (an
+ * invalid scale clears the row; NaN -> 0; +Inf -> 1).  One plane [M, bwta_plane_row_words(K)],
+ * pad bits zero; it is the `mask` of an operand with no sign plane.
+ */
+int bwta_quantize_pack_bool(const void *A, int64_t lda, const void *s_a, int scale_mode, int M, int K,
+                            uint32_t *mask, bwta_stream_t stream);
+
+/*
+ * The attention MatMuls of the paper ("Basic Layers for Linear and MatMul": the BWTA_QK and
+ * BWTA_Att rules; arithmetic Cases 3 and 2), batched over heads:
+ *   acc[b, m, n] = sum_k a[b, m, k] * b[b, n, k]        a, b in {-1, 0, +1} given as bit planes
+ *   out[b, m, n] = fp16( acc * fp32( alpha * (s_a * s_b) ) )   one rounding of the scale product
+ *                                                              to fp32, one of the result to fp16
+ * Both operands are K-major packed planes as produced by bwta_quantize_pack_act ([rows,
+ * bwta_plane_row_words(K)] words, batches `strideA` / `strideB` words apart).  A NULL sign plane
+ * means the operand is boolean (bwta_quantize_pack_bool): bool x ternary is the BWTA_Att rule
+ * popc(Att & V+) - popc(Att & V-); two ternary operands give the BWTA_QK rule.  For Q K^T pass
+ * Q as A [S, D] and K as B [S, D] with alpha = 1 / sqrt(D); for Att V pass Att as A [S, S] and V
+ * TRANSPOSED ([D, S], packed along the sequence) as B.
+ *   s_a, s_b   fp16 scales; VECTOR means one per row of every batch ([batch, M] / [batch, N]).
+ *   acc        optional int32 [batch, M, N] (dense); out optional fp16, row stride ldo >= N,
+ *              batches stride_out elements apart.  At least one of acc / out.
+ * Errors as bwta_gemm; nothing is enqueued on error.
+ */
+int bwta_matmul_tt(const uint32_t *maskA, const uint32_t *signA, int64_t strideA, const uint32_t *maskB,
+                   const uint32_t *signB, int64_t strideB, int batch, int M, int N, int K, const void *s_a,
+                   int a_scale_mode, const void *s_b, int b_scale_mode, float alpha, int32_t *acc, void *out,
+                   int64_t ldo, int64_t stride_out, bwta_stream_t stream);
+
 const char *bwta_strerror(int code);
 /* hipError_t value behind the calling thread's most recent BWTA_ERR_HIP (0 if none). */
 int bwta_last_hip_error(void);

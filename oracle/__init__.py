@@ -60,6 +60,9 @@ def lib():
         L.bwta_oracle_gemm_unpacked.argtypes = [P, P, c.c_int, c.c_int, c.c_int, P]
         L.bwta_oracle_gemm_packed.argtypes = [c.c_int, P, P, P, c.c_int, c.c_int, c.c_int, P]
         L.bwta_oracle_epilogue.argtypes = [P, P, c.c_int, P, c.c_int, c.c_int, c.c_int, P, c.c_int64]
+        L.bwta_oracle_boolize.argtypes = [P, c.c_int64, P, c.c_int, c.c_int, c.c_int, P]
+        L.bwta_oracle_matmul_tt_packed.argtypes = [c.c_int, P, P, P, P, c.c_int, c.c_int, c.c_int, P]
+        L.bwta_oracle_epilogue_alpha.argtypes = [P, P, c.c_int, P, c.c_int, c.c_float, c.c_int, c.c_int, P, c.c_int64]
         _lib = L
     return _lib
 
@@ -213,6 +216,42 @@ def epilogue(acc, s_a=None, s_w=None):
     out = np.empty((M, N), np.uint16)
     lib().bwta_oracle_epilogue(_p(acc), _p(sa), _scale_mode(sa, M), _p(sw), _scale_mode(sw, N),
                                M, N, _p(out), N)
+    return out.view(np.float16)
+
+
+def boolize(A, s_a=None):
+    """fp16 [M, K] (+ scale None / [1] / [M]) -> int8 [M, K] in {0, 1} by the bool function."""
+    Ab = _half_bits(A)
+    M, K = Ab.shape
+    sb = _half_bits(s_a)
+    b = np.empty((M, K), np.int8)
+    lib().bwta_oracle_boolize(_p(Ab), K, _p(sb), _scale_mode(sb, M), M, K, _p(b))
+    return b
+
+
+def matmul_tt_packed(form, maskA, signA, maskB, signB, K):
+    """a . b^T from (mask, sign) planes of both operands (sign None = boolean operand);
+    form 0 four-AND (Cases 3 / 2), form 1 popc(u) - 2 popc(u & (sA ^ sB))."""
+    maskA = np.ascontiguousarray(maskA, np.uint32)
+    maskB = np.ascontiguousarray(maskB, np.uint32)
+    signA = None if signA is None else np.ascontiguousarray(signA, np.uint32)
+    signB = None if signB is None else np.ascontiguousarray(signB, np.uint32)
+    M, N = maskA.shape[0], maskB.shape[0]
+    assert maskA.shape[1] == row_words(K) == maskB.shape[1]
+    acc = np.empty((M, N), np.int32)
+    lib().bwta_oracle_matmul_tt_packed(int(form), _p(maskA), None if signA is None else _p(signA), _p(maskB),
+                                       None if signB is None else _p(signB), M, N, K, _p(acc))
+    return acc
+
+
+def epilogue_alpha(acc, s_a=None, s_b=None, alpha=1.0):
+    """fp16( acc * fp32(alpha * (s_a[m] * s_b[n])) ); returns a float16 array [M, N]."""
+    acc = np.ascontiguousarray(acc, np.int32)
+    M, N = acc.shape
+    sa, sb = _half_bits(s_a), _half_bits(s_b)
+    out = np.empty((M, N), np.uint16)
+    lib().bwta_oracle_epilogue_alpha(_p(acc), _p(sa), _scale_mode(sa, M), _p(sb), _scale_mode(sb, N),
+                                     float(np.float32(alpha)), M, N, _p(out), N)
     return out.view(np.float16)
 
 

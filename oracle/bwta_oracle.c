@@ -294,6 +294,66 @@ void bwta_oracle_epilogue(const int32_t *acc, const uint16_t *s_a, int a_mode, c
     }
 }
 
+/* ---- attention MatMuls ("Basic Layers for Linear and MatMul": BWTA_QK and BWTA_Att) ------- */
+
+/* A: fp16 bits [M, lda] -> b int8 [M, K] in {0, 1} by the bool function. */
+void bwta_oracle_boolize(const uint16_t *A, int64_t lda, const uint16_t *s_a, int scale_mode, int M, int K,
+                         int8_t *b)
+{
+#pragma omp parallel for schedule(static)
+    for (int m = 0; m < M; ++m) {
+        double s = scale_value(s_a, scale_mode, m);
+        for (int k = 0; k < K; ++k)
+            b[(int64_t)m * K + k] = (int8_t)bwta_oracle_bool_value(bwta_oracle_half_to_double(A[m * lda + k]), s);
+    }
+}
+
+/* Packed evaluations of a[m,:] . b[n,:] for two operands given as (mask, sign) planes; a sign
+ * pointer may be NULL (boolean operand).  form 0: the four-AND expression of arithmetic Case 3,
+ * popc(A+ & B+) + popc(A- & B-) - popc(A+ & B-) - popc(A- & B+); with A- = 0 it is Case 2,
+ * popc(Att & V+) - popc(Att & V-).  form 1: popc(u) - 2 popc(u & (sA ^ sB)), u = maskA & maskB.
+ * For invariants only; the definition is bwta_oracle_gemm_unpacked on the unpacked operands. */
+void bwta_oracle_matmul_tt_packed(int form, const uint32_t *maskA, const uint32_t *signA, const uint32_t *maskB,
+                                  const uint32_t *signB, int M, int N, int K, int32_t *acc)
+{
+    int64_t rw = bwta_oracle_row_words(K);
+#pragma omp parallel for schedule(static)
+    for (int m = 0; m < M; ++m)
+        for (int n = 0; n < N; ++n) {
+            int32_t sum = 0;
+            for (int64_t q = 0; q < rw; ++q) {
+                uint32_t ma = maskA[m * rw + q], sa = signA ? signA[m * rw + q] & ma : 0u;
+                uint32_t mb = maskB[n * rw + q], sb = signB ? signB[n * rw + q] & mb : 0u;
+                if (form == 0) {
+                    uint32_t ap = ma ^ sa, an = sa, bp = mb ^ sb, bn = sb;
+                    sum += count_bits(ap & bp) + count_bits(an & bn) - count_bits(ap & bn) - count_bits(an & bp);
+                } else {
+                    uint32_t u = ma & mb;
+                    sum += count_bits(u) - 2 * count_bits(u & (sa ^ sb));
+                }
+            }
+            acc[(int64_t)m * N + n] = sum;
+        }
+}
+
+/* out[m, n] = fp16( acc[m, n] * s ),  s = fp32( alpha * (s_a[m] * s_b[n]) ): the scale prefix of the
+ * BWTA_QK rule (alpha = 1/sqrt(D), given as an fp32 number) and of the BWTA_Att rule (alpha = 1).
+ * s_a * s_b is exact (two 11-bit significands); the product with alpha is formed exactly in double
+ * (24 + 22 bits) and rounded once to fp32; acc * s is exact in double and rounded once to fp16. */
+void bwta_oracle_epilogue_alpha(const int32_t *acc, const uint16_t *s_a, int a_mode, const uint16_t *s_b,
+                                int b_mode, float alpha, int M, int N, uint16_t *out, int64_t ldo)
+{
+#pragma omp parallel for schedule(static)
+    for (int m = 0; m < M; ++m) {
+        double sa = scale_value(s_a, a_mode, m);
+        for (int n = 0; n < N; ++n) {
+            double sb = scale_value(s_b, b_mode, n);
+            float s = (float)((double)alpha * (sa * sb));
+            out[(int64_t)m * ldo + n] = bwta_oracle_double_to_half((double)acc[(int64_t)m * N + n] * (double)s);
+        }
+    }
+}
+
 /* The whole layer on fp16 activations and unpacked +-1 weights:
  * ternarise -> triple-loop product -> scale epilogue.  t_out/acc_out may be NULL. */
 void bwta_oracle_linear(const uint16_t *A, int64_t lda, const uint16_t *s_a, int a_mode,

@@ -23,7 +23,8 @@ PATH_AUTO, PATH_POPC, PATH_MFMA, PATH_FP4 = 0, 1, 2, 3
 EXPORTS = ["bwta_plane_row_words", "bwta_workspace_bytes", "bwta_quantize_pack_act",
            "bwta_pack_weights", "bwta_gemm", "bwta_linear", "bwta_strerror", "bwta_last_hip_error",
            "bwta_set_path", "bwta_get_path", "bwta_auto_path", "bwta_version", "bwta_set_tile",
-           "bwta_prepared_bytes", "bwta_prepare_act", "bwta_gemm_prepared", "bwta_gemm_grouped"]
+           "bwta_prepared_bytes", "bwta_prepare_act", "bwta_gemm_prepared", "bwta_gemm_grouped",
+           "bwta_quantize_pack_bool", "bwta_matmul_tt"]
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -64,6 +65,11 @@ class GemmProblem(_c.Structure):
 _lib.bwta_gemm_grouped.restype = _c.c_int
 _lib.bwta_gemm_grouped.argtypes = [_c.POINTER(GemmProblem), _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int,
                                    _c.c_int64, _P, _c.c_size_t, _P]
+_lib.bwta_quantize_pack_bool.restype = _c.c_int
+_lib.bwta_quantize_pack_bool.argtypes = [_P, _c.c_int64, _P, _c.c_int, _c.c_int, _c.c_int, _P, _P]
+_lib.bwta_matmul_tt.restype = _c.c_int
+_lib.bwta_matmul_tt.argtypes = [_P, _P, _c.c_int64, _P, _P, _c.c_int64, _c.c_int, _c.c_int, _c.c_int, _c.c_int,
+                                _P, _c.c_int, _P, _c.c_int, _c.c_float, _P, _P, _c.c_int64, _c.c_int64, _P]
 _lib.bwta_strerror.restype = _c.c_char_p
 _lib.bwta_strerror.argtypes = [_c.c_int]
 _lib.bwta_last_hip_error.restype = _c.c_int
@@ -182,6 +188,24 @@ def bwta_linear(A, s_a, wsign, s_w, out, workspace, *, M, N, K, lda=None, ldo=No
     _check(_lib.bwta_linear(_ptr(A), lda, _ptr(s_a), _mode(s_a, a_scale_mode), _ptr(wsign), _ptr(s_w),
                             _mode(s_w, w_scale_mode), M, N, K, _ptr(out), ldo, _ptr(workspace),
                             workspace_bytes, _stream(stream)))
+
+
+def bwta_quantize_pack_bool(A, s_a, mask, *, M, K, lda=None, scale_mode=None, stream=None):
+    lda = K if lda is None else lda
+    _check(_lib.bwta_quantize_pack_bool(_ptr(A), lda, _ptr(s_a), _mode(s_a, scale_mode), M, K, _ptr(mask),
+                                        _stream(stream)))
+
+
+def bwta_matmul_tt(maskA, signA, maskB, signB, s_a, s_b, acc, out, *, batch, M, N, K, alpha=1.0, strideA=None,
+                   strideB=None, ldo=None, stride_out=None, a_scale_mode=None, b_scale_mode=None, stream=None):
+    rw = plane_row_words(K)
+    strideA = M * rw if strideA is None else strideA
+    strideB = N * rw if strideB is None else strideB
+    ldo = N if ldo is None else ldo
+    stride_out = M * ldo if stride_out is None else stride_out
+    _check(_lib.bwta_matmul_tt(_ptr(maskA), _ptr(signA), strideA, _ptr(maskB), _ptr(signB), strideB, batch, M, N, K,
+                               _ptr(s_a), _mode(s_a, a_scale_mode), _ptr(s_b), _mode(s_b, b_scale_mode), float(alpha),
+                               _ptr(acc), _ptr(out), ldo, stride_out, _stream(stream)))
 
 
 def _nbytes(buf, given):

@@ -257,6 +257,46 @@ int bwta_gemm_grouped(const bwta_gemm_problem *problems, int count, int M, int N
     return BWTA_OK;
 }
 
+int bwta_quantize_pack_bool(const void *A, int64_t lda, const void *s_a, int scale_mode, int M, int K,
+                            uint32_t *mask, bwta_stream_t stream)
+{
+    if (!scale_mode_ok(scale_mode)) return BWTA_ERR_UNSUPPORTED;
+    if (M < 0 || K < 0 || (M > 0 && K == 0)) return BWTA_ERR_SHAPE;
+    if (M == 0) return BWTA_OK;
+    if (lda < K) return BWTA_ERR_SHAPE;
+    if (!A || !mask) return BWTA_ERR_NULL;
+    if (scale_mode != BWTA_SCALE_NONE && !s_a) return BWTA_ERR_NULL;
+    if (!aligned(mask, 16) || !aligned(A, 2) || (s_a && !aligned(s_a, 2))) return BWTA_ERR_ALIGN;
+    bwta::ScaleArg sa{(const uint16_t *)s_a, s_a ? scale_mode : BWTA_SCALE_NONE};
+    return hip_result(bwta::launch_quantize_pack_bool(A, lda, sa, M, K, mask, (hipStream_t)stream));
+}
+
+int bwta_matmul_tt(const uint32_t *maskA, const uint32_t *signA, int64_t strideA, const uint32_t *maskB,
+                   const uint32_t *signB, int64_t strideB, int batch, int M, int N, int K, const void *s_a,
+                   int a_scale_mode, const void *s_b, int b_scale_mode, float alpha, int32_t *acc, void *out,
+                   int64_t ldo, int64_t stride_out, bwta_stream_t stream)
+{
+    int rc = check_gemm_common(M, N, K, s_a, a_scale_mode, s_b, b_scale_mode, out, ldo);
+    if (rc != BWTA_OK) return rc;
+    if (batch < 0) return BWTA_ERR_SHAPE;
+    if (batch == 0 || M == 0 || N == 0) return BWTA_OK;
+    if (batch > 65535) return BWTA_ERR_UNSUPPORTED;  // grid.z
+    if (!(alpha == alpha) || alpha - alpha != 0.0f) return BWTA_ERR_UNSUPPORTED;  // NaN / Inf
+    if (!maskA || !maskB || (!acc && !out)) return BWTA_ERR_NULL;
+    const int64_t rw = bwta_plane_row_words(K);
+    if (batch > 1 && (strideA < (int64_t)M * rw || strideB < (int64_t)N * rw)) return BWTA_ERR_SHAPE;
+    if (out && batch > 1 && stride_out < (int64_t)(M - 1) * ldo + N) return BWTA_ERR_SHAPE;
+    if ((strideA & 3) || (strideB & 3)) return BWTA_ERR_ALIGN;  // batches keep the 16-byte alignment
+    if (!aligned(maskA, 16) || !aligned(maskB, 16) || (signA && !aligned(signA, 16)) ||
+        (signB && !aligned(signB, 16)) || (acc && !aligned(acc, 4)))
+        return BWTA_ERR_ALIGN;
+    bwta::MatmulTTArgs g{maskA, signA, maskB, signB, strideA, strideB, batch, M, N, K, (int)rw,
+                         {(const uint16_t *)s_a, s_a ? a_scale_mode : BWTA_SCALE_NONE},
+                         {(const uint16_t *)s_b, s_b ? b_scale_mode : BWTA_SCALE_NONE},
+                         alpha, acc, (uint16_t *)out, ldo, (int64_t)M * N, stride_out};
+    return hip_result(bwta::launch_matmul_tt(g, (hipStream_t)stream));
+}
+
 const char *bwta_strerror(int code)
 {
     switch (code) {

@@ -20,7 +20,22 @@ struct GemmArgs {
     int64_t ldo;
 };
 
+// batched ternary x ternary / bool x ternary product (attention MatMuls)
+struct MatmulTTArgs {
+    const uint32_t *maskA, *signA, *maskB, *signB;  // sign planes nullable (boolean operand)
+    int64_t strideA, strideB;                       // words between batches
+    int batch, M, N, K, rw;
+    ScaleArg s_a, s_b;  // VECTOR: [batch][M] / [batch][N]
+    float alpha;
+    int32_t *acc;   // nullable, [batch][M][N] with stride_acc
+    uint16_t *out;  // nullable, fp16 bits
+    int64_t ldo, stride_acc, stride_out;
+};
+
 // launchers (each returns the launch's hipError_t)
+hipError_t launch_matmul_tt(const MatmulTTArgs &g, hipStream_t st);
+hipError_t launch_quantize_pack_bool(const void *A, int64_t lda, ScaleArg s_a, int M, int K, uint32_t *mask,
+                                     hipStream_t st);
 hipError_t launch_quantize_pack(const void *A, int dtype, int64_t lda, ScaleArg s_a, int M, int K,
                                 uint32_t *mask, uint32_t *sign, int32_t *nnz, hipStream_t st);
 hipError_t launch_pack_weights(const void *W, int dtype, int64_t ldw, int N, int K, uint32_t *wsign,

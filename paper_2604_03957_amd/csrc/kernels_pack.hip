@@ -38,7 +38,7 @@ __device__ __forceinline__ TernaryBits ternary_bits_fp16(const uint16_t v[8], in
     return r;
 }
 
-template <int DTYPE>  // 0 = fp16 activations, 1 = int8 ternary activations
+template <int DTYPE>  // 0 = fp16 -> ternary, 1 = int8 ternary, 2 = fp16 -> boolean (the bool function: 1 iff a >= 0.5 s)
 __global__ __launch_bounds__(kThreads) void k_quantize_pack(const void *__restrict__ A, int64_t lda,
                                                             ScaleArg s_a, int M, int K, int rw,
                                                             uint32_t *__restrict__ mask,
@@ -53,7 +53,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack(const void *__restri
     const int k0 = c * 8;
     const int nvalid = K - k0 >= 8 ? 8 : (K - k0 > 0 ? K - k0 : 0);
     TernaryBits tb{0u, 0u};
-    if (DTYPE == 0) {
+    if (DTYPE == 0 || DTYPE == 2) {
         const uint16_t *row = (const uint16_t *)A + (int64_t)m * lda;
         uint16_t v[8];
         if (nvalid == 8 && vec_ok) {
@@ -67,6 +67,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack(const void *__restri
         float s = load_scale(s_a, m);
         bool ok = (s > 0.0f) && (s < __builtin_inff());
         tb = ternary_bits_fp16(v, nvalid, 0.5f * s, ok);
+        if (DTYPE == 2) tb.nz &= ~tb.neg;  // boolean: only a >= 0.5 s counts, and there is no sign plane
     } else {
         const int8_t *row = (const int8_t *)A + (int64_t)m * lda;
         int8_t v[8];
@@ -92,7 +93,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack(const void *__restri
     uint32_t ws = quad_word(tb.neg, lane);
     const int64_t widx = (int64_t)m * rw + (c >> 2);
     if ((lane & 3) == 0) mask[widx] = wm;
-    if ((lane & 3) == 1) sign[widx] = ws;
+    if (DTYPE != 2 && (lane & 3) == 1) sign[widx] = ws;
 }
 
 template <int DTYPE>
@@ -181,6 +182,19 @@ hipError_t launch_quantize_pack(const void *A, int dtype, int64_t lda, ScaleArg 
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || nnz == nullptr) return e;
     hipLaunchKernelGGL(k_row_popcount, dim3((M + 3) / 4), dim3(kThreads), 0, st, mask, M, rw, nnz);
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_pack_bool(const void *A, int64_t lda, ScaleArg s_a, int M, int K, uint32_t *mask,
+                                     hipStream_t st)
+{
+    const int rw = 4 * ((K + 127) / 128);
+    const int64_t total = (int64_t)M * rw * 4;
+    if (total == 0) return hipSuccess;
+    const unsigned grid = (unsigned)((total + kThreads - 1) / kThreads);
+    const int vec_ok = (((uintptr_t)A % 16) == 0 && (lda % 8) == 0) ? 1 : 0;
+    hipLaunchKernelGGL(k_quantize_pack<2>, dim3(grid), dim3(kThreads), 0, st, A, lda, s_a, M, K, rw, mask,
+                       (uint32_t *)nullptr, vec_ok);
     return hipGetLastError();
 }
 

@@ -109,3 +109,24 @@ def test_prepare_and_gemm_prepared_reject_bad_arguments():
     assert _code(g, FAKE, None, FAKE, FAKE, None, FAKE, **kw) == B.ERR_NULL
     assert _code(g, FAKE, FAKE, FAKE, FAKE, None, None, **kw) == B.ERR_NULL
     assert _code(g, FAKE, FAKE, FAKE, FAKE, None, FAKE, **dict(kw, ldo=4)) == B.ERR_SHAPE
+
+
+def test_attention_entry_points_reject_bad_arguments():
+    qb = B.bwta_quantize_pack_bool
+    kw = dict(M=4, K=256, stream=0, scale_mode=B.SCALE_SCALAR)
+    assert _code(qb, None, FAKE, FAKE, **kw) == B.ERR_NULL
+    assert _code(qb, FAKE, None, FAKE, **kw) == B.ERR_NULL
+    assert _code(qb, FAKE, FAKE, FAKE + 8, **kw) == B.ERR_ALIGN
+    assert _code(qb, FAKE, FAKE, FAKE, **dict(kw, lda=100)) == B.ERR_SHAPE
+    qb(FAKE, FAKE, FAKE, **dict(kw, M=0))                                   # empty: nothing enqueued
+    mm = B.bwta_matmul_tt
+    kw = dict(batch=2, M=8, N=8, K=128, stream=0, a_scale_mode=B.SCALE_NONE, b_scale_mode=B.SCALE_NONE)
+    assert _code(mm, None, FAKE, FAKE, FAKE, None, None, FAKE, FAKE, **kw) == B.ERR_NULL
+    assert _code(mm, FAKE, None, FAKE, None, None, None, None, None, **kw) == B.ERR_NULL      # no output at all
+    assert _code(mm, FAKE, FAKE + 4, FAKE, FAKE, None, None, FAKE, FAKE, **kw) == B.ERR_ALIGN
+    assert _code(mm, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, FAKE, **dict(kw, strideA=8)) == B.ERR_SHAPE
+    assert _code(mm, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, FAKE, **dict(kw, strideA=8 * 4 + 2)) == B.ERR_ALIGN
+    assert _code(mm, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, FAKE, **dict(kw, ldo=4)) == B.ERR_SHAPE
+    assert _code(mm, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, FAKE, **dict(kw, alpha=float("inf"))) == B.ERR_UNSUPPORTED
+    assert _code(mm, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, FAKE, **dict(kw, batch=-1)) == B.ERR_SHAPE
+    mm(FAKE, FAKE, FAKE, FAKE, None, None, FAKE, FAKE, **dict(kw, batch=0))  # empty batch: nothing enqueued

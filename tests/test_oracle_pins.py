@@ -274,3 +274,100 @@ def test_linear_is_the_composition():
     assert np.array_equal(acc, t.astype(np.int64) @ c["w"].astype(np.int64).T)
     ref = acc.astype(np.float64) * c["s_a"].astype(np.float64)[:, None] * c["s_w"].astype(np.float64)[None, :]
     assert np.allclose(out.astype(np.float64), ref, rtol=2.0 ** -11, atol=0)
+
+
+# ---- attention MatMuls (BWTA_QK: ternary x ternary; BWTA_Att: bool x ternary) -----------------
+
+def test_boolize_every_half_pattern_and_ties():
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16).reshape(1, -1)
+    A = bits.view(np.float16)
+    for s in (1.0, 0.5, 1.5, 2.0 ** -24, 65504.0):
+        got = oracle.boolize(A, np.array([s], np.float16))[0]
+        a = A[0].astype(np.float64)
+        with np.errstate(invalid="ignore"):
+            want = np.where(np.isnan(a), 0, (a >= 0.5 * float(np.float16(s))).astype(np.int8))
+        assert np.array_equal(got, want), s
+    # exactly 0.5 s -> 1 (the >= of the printed rule); just below -> 0; negative scale clears the row
+    assert oracle.boolize(np.array([[0.75, 0.7495]], np.float16), np.array([1.5], np.float16)).tolist() == [[1, 0]]
+    assert oracle.boolize(np.array([[5.0]], np.float16), np.array([-1.0], np.float16)).tolist() == [[0]]
+    # bool(a) agrees with the positive part of ternary(a)
+    x = synth.gaussian(5, 9, 4096).astype(np.float16).reshape(4, -1)
+    s = np.array([0.7], np.float16)
+    assert np.array_equal(oracle.boolize(x, s), (oracle.ternarize(x, s) == 1).astype(np.int8))
+
+
+def _tt_forms(a, b, a_bool=False):
+    K = a.shape[1]
+    ma, sa, _ = oracle.pack_act(a)
+    mb, sb, _ = oracle.pack_act(b)
+    if a_bool:
+        assert not sa.any()
+        sa = None
+    return [oracle.gemm_unpacked(a, b)] + [oracle.matmul_tt_packed(f, ma, sa, mb, sb, K) for f in (0, 1)]
+
+
+@pytest.mark.parametrize("K", [1, 2, 3, 4])
+def test_ternary_ternary_brute_force_every_operand_pair(K):
+    t = np.array(list(itertools.product((-1, 0, 1), repeat=K)), np.int8)       # 3^K rows on both sides
+    want = t.astype(np.int64) @ t.astype(np.int64).T
+    for got in _tt_forms(t, t):
+        assert np.array_equal(got, want)
+    b = np.array(list(itertools.product((0, 1), repeat=K)), np.int8)           # 2^K boolean rows
+    want = b.astype(np.int64) @ t.astype(np.int64).T
+    for got in _tt_forms(b, t, a_bool=True):
+        assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("K", [1, 31, 32, 33, 127, 128, 129, 2048])
+def test_attention_products_equal_numpy_matmul(K):
+    q = synth.ternary(31, K, (10, K), 0.4)
+    k = synth.ternary(31, 700 + K, (13, K), 0.55)
+    want = q.astype(np.int64) @ k.astype(np.int64).T
+    for got in _tt_forms(q, k):
+        assert got.dtype == np.int32 and np.array_equal(got, want)
+    att = (synth.ternary(32, K, (10, K), 0.7) != 0).astype(np.int8)            # boolean, ~30 % ones
+    want = att.astype(np.int64) @ k.astype(np.int64).T
+    for got in _tt_forms(att, k, a_bool=True):
+        assert np.array_equal(got, want)
+
+
+def test_attention_product_invariants():
+    K = 200
+    q = synth.ternary(33, 1, (7, K), 0.4)
+    k = synth.ternary(33, 2, (9, K), 0.4)
+    ma, sa, _ = oracle.pack_act(q)
+    mb, sb, _ = oracle.pack_act(k)
+    base = oracle.matmul_tt_packed(1, ma, sa, mb, sb, K)
+    assert np.array_equal(base.T, oracle.matmul_tt_packed(1, mb, sb, ma, sa, K))           # symmetry of the rule
+    assert np.array_equal(oracle.gemm_unpacked(-q, k), -base)                               # sign flips
+    dirty_a = sa | (~ma & np.uint32(0xA5A5A5A5))                                            # sign bits under a zero mask
+    dirty_b = sb | (~mb & np.uint32(0x5A5A5A5A))
+    for f in (0, 1):
+        assert np.array_equal(oracle.matmul_tt_packed(f, ma, dirty_a, mb, dirty_b, K), base)
+    # a binary (+-1) second operand reduces the rule to the BWTA linear product
+    w = synth.binary_pm1(33, 3, (9, K))
+    mw, sw, _ = oracle.pack_act(w)
+    assert np.array_equal(oracle.matmul_tt_packed(1, ma, sa, mw, sw, K), oracle.gemm_packed(0, ma, sa, oracle.pack_weights(w), K))
+    # |acc| <= number of positions where both are non-zero, and same parity
+    both = (q != 0).astype(np.int64) @ (k != 0).astype(np.int64).T
+    assert np.all(np.abs(base) <= both) and np.all((base - both) % 2 == 0)
+
+
+def test_epilogue_alpha_against_exact_rational_arithmetic():
+    rng = np.random.default_rng(9)
+    M, N = 6, 30
+    acc = rng.integers(-2048, 2049, (M, N)).astype(np.int32)
+    s_a, s_b = synth.scales(9, 1, M), synth.scales(9, 2, N)
+    alpha = np.float32(1.0 / math.sqrt(128.0))
+    got = oracle.epilogue_alpha(acc, s_a, s_b, alpha)
+    for m in range(M):
+        for n in range(N):
+            prod = Fraction(float(alpha)) * Fraction(float(s_a[m])) * Fraction(float(s_b[n]))
+            s32 = np.float32(float(prod))            # the exact product (46 bits) fits a double; one rounding to fp32
+            assert Fraction(float(prod)) == prod
+            exact = Fraction(int(acc[m, n])) * Fraction(float(s32))
+            assert Fraction(float(exact)) == exact
+            want = np.float64(float(exact)).astype(np.float16)
+            assert got[m, n].view(np.uint16) == want.view(np.uint16), (m, n)
+    # alpha = 1 reduces to the linear layer's epilogue
+    assert np.array_equal(oracle.epilogue_alpha(acc, s_a, s_b, 1.0).view(np.uint16), oracle.epilogue(acc, s_a, s_b).view(np.uint16))
