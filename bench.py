@@ -10,7 +10,7 @@ layers.  Inputs are resident in HBM before the timed region; weights are packed 
 Prints ONE JSON line.  `value` is effective TOPS = 2*M*N*K summed over the step / time
 (zeros counted, dense-equivalent work).  `roofline` is for the dominant kernel, timed live
 with HIP events on the launch stream; `cpu_baseline` is the CPU oracle timed on the host
-cores of the same box.  Other workloads: --workload c1_tiny | c3_prefill | c4_decode | c5_block | copy_probe.
+cores of the same box.  Other workloads: --workload c1_tiny | c3_prefill | c4_decode | c5_block | attn | copy_probe.
 """
 import argparse
 import json
@@ -286,6 +286,62 @@ def run_c4(args, torch, B, synth):
             "kernels": res}
 
 
+def run_attn(args, torch, B, synth):
+    """The two attention MatMuls at the decoder block's shapes: 32 heads, 2048 tokens, head dim 128.
+    Operands are packed once (ternary Q, K, V^T; boolean Att with ~10 % ones, like thresholded
+    attention probabilities); the products are timed alone and with their packers."""
+    H, S, D = 32, 2048, 128
+    dev = "cuda:0"
+    rw_d, rw_s = B.plane_row_words(D), B.plane_row_words(S)
+    q = _dev(synth.laplace_activations(6, 1, H * S, D), torch)
+    k = _dev(synth.laplace_activations(6, 2, H * S, D), torch)
+    vt = _dev(synth.laplace_activations(6, 3, H * D, S), torch)
+    # one head's |N(0,1)| * 0.3 against a threshold of 0.5: 9.5 % ones; the same head repeated for all heads
+    att = _dev((np.abs(synth.gaussian(6, 4, S * S)) * 0.3).astype(np.float16).reshape(S, S), torch).repeat(H, 1)
+    one = torch.ones(1, dtype=torch.float16, device=dev)
+    s_att = torch.full((1,), 1.0, dtype=torch.float16, device=dev)
+    planes = lambda rows, rw: (torch.empty((rows, rw), dtype=torch.int32, device=dev), torch.empty((rows, rw), dtype=torch.int32, device=dev))
+    qm, qs = planes(H * S, rw_d)
+    km, ks = planes(H * S, rw_d)
+    vm, vs = planes(H * D, rw_s)
+    am, _ = planes(H * S, rw_s)
+    scores = torch.empty((H, S, S), dtype=torch.float16, device=dev)
+    ctx = torch.empty((H, S, D), dtype=torch.float16, device=dev)
+
+    def pack_qk():
+        B.bwta_quantize_pack_act(q, one, qm, qs, None, M=H * S, K=D)
+        B.bwta_quantize_pack_act(k, one, km, ks, None, M=H * S, K=D)
+
+    def pack_att_v():
+        B.bwta_quantize_pack_bool(att, s_att, am, M=H * S, K=S)
+        B.bwta_quantize_pack_act(vt, one, vm, vs, None, M=H * D, K=S)
+
+    def qk():
+        B.bwta_matmul_tt(qm, qs, km, ks, one, one, None, scores, batch=H, M=S, N=S, K=D, alpha=1.0 / D ** 0.5)
+
+    def av():
+        B.bwta_matmul_tt(am, None, vm, vs, s_att, one, None, ctx, batch=H, M=S, N=D, K=S)
+
+    pack_qk(); pack_att_v(); torch.cuda.synchronize()
+    steps = max(5, args.steps // 10)
+    t = {n: _event_ms(torch, f, steps, 2) for n, f in (("pack_qk", pack_qk), ("qk", qk), ("pack_att_v", pack_att_v), ("att_v", av))}
+    ops = 2.0 * H * S * S * D
+    total = sum(t.values())
+    peak_alu = PEAK_VALU_POPC_TOPS / 2  # 4 vector-ALU operations per 32 multiply-accumulates instead of 2
+    kern = {n + "_us": round(v * 1e3, 1) for n, v in t.items()}
+    kern.update(qk_TOPS=round(ops / (t["qk"] * 1e-3) / 1e12, 1), att_v_TOPS=round(ops / (t["att_v"] * 1e-3) / 1e12, 1))
+    achieved = 2 * ops / ((t["qk"] + t["att_v"]) * 1e-3) / 1e12
+    return {"metric": "BWTA attention MatMuls effective TOPS (QK^T and Att V, 32 heads x 2048 x 128)",
+            "value": round(achieved, 1), "unit": "TOPS", "n_gpus": 1, "steps": steps, "warmup": 2,
+            "ms_per_step": round(total, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "int32 (popcount)", "data": "synthetic",
+            "config": {"workload": "attn: BWTA_QK ternary x ternary [2048,128]x[128,2048] and BWTA_Att bool x ternary "
+                                   "[2048,2048]x[2048,128], 32 heads"},
+            "roofline": {"bound": "alu", "achieved": round(achieved, 1), "peak": peak_alu, "unit": "TOP/s",
+                         "frac": round(achieved / peak_alu, 4), "traffic": None},
+            "kernels": kern}
+
+
 def run_c1(args, torch, B, synth):
     c = synth.config1()
     L = Layer(c, torch, B, from_fp16=False)
@@ -417,7 +473,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c2_ffn", choices=["c2_ffn", "c1_tiny", "c3_prefill", "c4_decode", "c5_block", "copy_probe"])
+    ap.add_argument("--workload", default="c2_ffn", choices=["c2_ffn", "c1_tiny", "c3_prefill", "c4_decode", "c5_block", "attn", "copy_probe"])
     ap.add_argument("--decode-matrices", type=int, default=64)
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--graph", action="store_true",
@@ -436,7 +492,7 @@ def main():
     from paper_2604_03957_amd import synth
     torch.cuda.set_device(0)
     run = {"c2_ffn": run_c2, "c1_tiny": run_c1, "c3_prefill": run_c3, "c4_decode": run_c4,
-           "c5_block": run_c5, "copy_probe": run_copy_probe}[args.workload]
+           "c5_block": run_c5, "attn": run_attn, "copy_probe": run_copy_probe}[args.workload]
     out = run(args, torch, B, synth)
     print(json.dumps(out), flush=True)
 

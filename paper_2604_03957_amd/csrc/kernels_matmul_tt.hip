@@ -60,6 +60,7 @@ __global__ __launch_bounds__(256) void k_matmul_tt(MatmulTTArgs g)
         __syncthreads();
 #pragma unroll
         for (int kk = 0; kk < KT; kk += 4) {
+            if (k0 + kk >= rw) break;  // short rows (head dimension 128 = 4 words): skip the zero padding
             uint4 xam[4], xas[4], xbm[4], xbs[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -87,18 +88,38 @@ __global__ __launch_bounds__(256) void k_matmul_tt(MatmulTTArgs g)
     uint16_t *out = g.out ? g.out + (int64_t)b * g.stride_out : nullptr;
     const ScaleArg sa{g.s_a.ptr && g.s_a.mode == 2 ? g.s_a.ptr + (int64_t)b * g.M : g.s_a.ptr, g.s_a.mode};
     const ScaleArg sb{g.s_b.ptr && g.s_b.mode == 2 ? g.s_b.ptr + (int64_t)b * g.N : g.s_b.ptr, g.s_b.mode};
+    // int32 results (tests, debugging) go out directly; fp16 results are gathered in LDS so that the
+    // tile leaves as 16-byte row-contiguous stores (the score matrix is the bulk of the traffic)
+    __shared__ __attribute__((aligned(16))) uint16_t sOut[BM][BN + 8];
+    const bool vec_ok = out && ((g.ldo & 7) == 0) && ((g.stride_out & 7) == 0) && (((uintptr_t)g.out & 15) == 0) &&
+                        (n0 + BN <= g.N);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int m = m0 + ty + 16 * i;
-        if (m >= g.M) continue;
-        const float fa = load_scale(sa, m);
+        const float fa = m < g.M ? load_scale(sa, m) : 0.f;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int n = n0 + tx + 16 * j;
-            if (n >= g.N) continue;
             const int a = both[i][j] - 2 * diff[i][j];
-            if (acc) acc[(int64_t)m * g.N + n] = a;
-            if (out) out[(int64_t)m * g.ldo + n] = scaled_to_half(a, g.alpha * (fa * load_scale(sb, n)));
+            if (m < g.M && n < g.N) {
+                if (acc) acc[(int64_t)m * g.N + n] = a;
+                if (out) {
+                    const uint16_t h = scaled_to_half(a, g.alpha * (fa * load_scale(sb, n)));
+                    if (vec_ok)
+                        sOut[ty + 16 * i][tx + 16 * j] = h;
+                    else
+                        out[(int64_t)m * g.ldo + n] = h;
+                }
+            }
+        }
+    }
+    if (vec_ok) {  // uniform over the workgroup
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int p = tid + 256 * r, row = p >> 3, c8 = 8 * (p & 7);  // 64 rows x 8 pieces of 8 halfs
+            if (m0 + row < g.M)
+                *(uint4 *)(out + (int64_t)(m0 + row) * g.ldo + n0 + c8) = *(const uint4 *)&sOut[row][c8];
         }
     }
 }
