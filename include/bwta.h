@@ -190,6 +190,25 @@ int bwta_matmul_tt(const uint32_t *maskA, const uint32_t *signA, int64_t strideA
                    int a_scale_mode, const void *s_b, int b_scale_mode, float alpha, int32_t *acc, void *out,
                    int64_t ldo, int64_t stride_out, bwta_stream_t stream);
 
+/*
+ * Binary weights from full-precision ones (the paper's W_sign equation), per output channel n:
+ *   mu_n = mean_k W[n, k];  wsign bit = 1 iff W[n, k] - mu_n < 0;  s_w[n] = fp16( mean_k |W[n, k] - mu_n| )
+ * W is fp16 [N, ldw]; wsign is written in the layout of bwta_pack_weights; s_w is fp16 [N] (the
+ * scale that minimises ||(W - mu) - s sign(W - mu)||^2; the printed (1/n)||W||_F is read as this
+ * l1 mean).  Sums are exact (binary16 values are integers in units of 2^-24), so the planes equal
+ * exact arithmetic bit for bit; the scale is rounded once from a double.  NaN / Inf entries stay
+ * out of the mean and the scale (+Inf -> +1, -Inf and NaN -> -1).  K <= 32768.
+ */
+int bwta_prepare_weights(const void *W, int64_t ldw, int N, int K, uint32_t *wsign, void *s_w,
+                         bwta_stream_t stream);
+
+/*
+ * The value the paper initialises the activation scale with (the s_A^0 equation), per token:
+ *   s[m] = fp16( 2 * mean_k |A[m, k]| )   A fp16 [M, lda], s fp16 [M]; exact sum, one rounding;
+ * NaN / Inf entries count as 0.  K <= 32768.
+ */
+int bwta_act_scale(const void *A, int64_t lda, int M, int K, void *s, bwta_stream_t stream);
+
 const char *bwta_strerror(int code);
 /* hipError_t value behind the calling thread's most recent BWTA_ERR_HIP (0 if none). */
 int bwta_last_hip_error(void);

@@ -63,6 +63,8 @@ def lib():
         L.bwta_oracle_boolize.argtypes = [P, c.c_int64, P, c.c_int, c.c_int, c.c_int, P]
         L.bwta_oracle_matmul_tt_packed.argtypes = [c.c_int, P, P, P, P, c.c_int, c.c_int, c.c_int, P]
         L.bwta_oracle_epilogue_alpha.argtypes = [P, P, c.c_int, P, c.c_int, c.c_float, c.c_int, c.c_int, P, c.c_int64]
+        L.bwta_oracle_prepare_weights.argtypes = [P, c.c_int64, c.c_int, c.c_int, P, P]
+        L.bwta_oracle_act_scale.argtypes = [P, c.c_int64, c.c_int, c.c_int, P]
         _lib = L
     return _lib
 
@@ -253,6 +255,25 @@ def epilogue_alpha(acc, s_a=None, s_b=None, alpha=1.0):
     lib().bwta_oracle_epilogue_alpha(_p(acc), _p(sa), _scale_mode(sa, M), _p(sb), _scale_mode(sb, N),
                                      float(np.float32(alpha)), M, N, _p(out), N)
     return out.view(np.float16)
+
+
+def prepare_weights(W):
+    """fp16 [N, K] -> (w int8 [N, K] = sign(W - row mean), s_w float16 [N] = row mean of |W - row mean|)."""
+    Wb = _half_bits(W)
+    N, K = Wb.shape
+    w = np.empty((N, K), np.int8)
+    s = np.empty(N, np.uint16)
+    lib().bwta_oracle_prepare_weights(_p(Wb), K, N, K, _p(w), _p(s))
+    return w, s.view(np.float16)
+
+
+def act_scale(A):
+    """fp16 [M, K] -> float16 [M]: 2 * mean_k |A[m, k]|, exact sum, one rounding."""
+    Ab = _half_bits(A)
+    M, K = Ab.shape
+    s = np.empty(M, np.uint16)
+    lib().bwta_oracle_act_scale(_p(Ab), K, M, K, _p(s))
+    return s.view(np.float16)
 
 
 def linear(A, s_a, w, s_w):

@@ -354,6 +354,85 @@ void bwta_oracle_epilogue_alpha(const int32_t *acc, const uint16_t *s_a, int a_m
     }
 }
 
+/* ---- weight preparation and the activation scale's starting value ------------------------- */
+
+/* A finite binary16 value as an integer count of 2^-24 (exact); 0 for NaN / Inf. */
+static int64_t half_fixed(uint16_t h, int *finite)
+{
+    int sign = (h >> 15) & 1, expo = (h >> 10) & 0x1f, frac = h & 0x3ff;
+    int64_t v;
+    *finite = expo != 31;
+    if (expo == 31) return 0;
+    v = expo == 0 ? (int64_t)frac : ((int64_t)(1024 + frac) << (expo - 1));
+    return sign ? -v : v;
+}
+
+/* num / den (den > 0) rounded once to binary16, ties to even, by integer arithmetic only. */
+static uint16_t ratio_to_half(unsigned __int128 num, unsigned __int128 den)
+{
+    if (num == 0) return 0;
+    int e = 16; /* largest e with 2^e <= num / den, searched downwards; values >= 2^16 overflow */
+    if (num >= (den << 16)) return 0x7c00;
+    while (e > -25) {
+        --e;
+        if (e >= 0 ? num >= (den << e) : (num << -e) >= den) break;
+    }
+    int qe = (e < -14 ? -14 : e) - 10; /* exponent of the spacing of binary16 numbers at this magnitude */
+    unsigned __int128 n2 = qe >= 0 ? num : num << -qe, d2 = qe >= 0 ? den << qe : den;
+    unsigned __int128 q = n2 / d2, r = n2 - q * d2;
+    if (2 * r > d2 || (2 * r == d2 && (q & 1))) ++q;
+    int expo = e < -14 ? -14 : e;
+    if (q >= 2048) { q = 1024; ++expo; }
+    if (expo > 15) return 0x7c00;
+    if (q < 1024) return (uint16_t)q; /* subnormal (or rounded up to the smallest normal: bits 0x400) */
+    return (uint16_t)(((expo + 15) << 10) | ((int)q - 1024));
+}
+
+/* Binary weights from full-precision ones (the W_sign equation): per output channel n,
+ *   mu_n = mean_k W[n, k],  w[n, k] = sign(W[n, k] - mu_n),  s_w[n] = mean_k |W[n, k] - mu_n|
+ * (the scale that minimises || (W - mu) - s sign(W - mu) ||^2; the printed (1/n)||W||_F is read as
+ * this l1 mean).  All decisions are exact: binary16 values are integers in units of 2^-24, so
+ * W[n,k] - mu_n >= 0 is the integer test K * W >= sum(W).  Non-finite entries do not enter the
+ * mean or the scale; +Inf -> +1, -Inf and NaN -> -1.  w: int8 [N, K]; s_w: fp16 bits [N]. */
+void bwta_oracle_prepare_weights(const uint16_t *W, int64_t ldw, int N, int K, int8_t *w, uint16_t *s_w)
+{
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        const uint16_t *row = W + (int64_t)n * ldw;
+        int64_t S = 0;
+        int fin;
+        for (int k = 0; k < K; ++k) S += half_fixed(row[k], &fin);
+        unsigned __int128 T = 0;
+        for (int k = 0; k < K; ++k) {
+            int64_t v = half_fixed(row[k], &fin);
+            if (!fin) {
+                w[(int64_t)n * K + k] = (row[k] == 0x7c00) ? 1 : -1;
+                continue;
+            }
+            __int128 d = (__int128)v * K - S;
+            w[(int64_t)n * K + k] = d >= 0 ? 1 : -1;
+            T += (unsigned __int128)(d >= 0 ? d : -d);
+        }
+        s_w[n] = ratio_to_half(T, ((unsigned __int128)K * K) << 24);
+    }
+}
+
+/* The value the activation scale starts from (the s_A^0 equation), per token:
+ *   s[m] = 2 * mean_k |A[m, k]|, exact sum, rounded once to binary16.  Non-finite entries count as 0. */
+void bwta_oracle_act_scale(const uint16_t *A, int64_t lda, int M, int K, uint16_t *s)
+{
+#pragma omp parallel for schedule(static)
+    for (int m = 0; m < M; ++m) {
+        unsigned __int128 T = 0;
+        int fin;
+        for (int k = 0; k < K; ++k) {
+            int64_t v = half_fixed(A[(int64_t)m * lda + k], &fin);
+            T += (unsigned __int128)(v >= 0 ? v : -v);
+        }
+        s[m] = ratio_to_half(2 * T, (unsigned __int128)K << 24);
+    }
+}
+
 /* The whole layer on fp16 activations and unpacked +-1 weights:
  * ternarise -> triple-loop product -> scale epilogue.  t_out/acc_out may be NULL. */
 void bwta_oracle_linear(const uint16_t *A, int64_t lda, const uint16_t *s_a, int a_mode,

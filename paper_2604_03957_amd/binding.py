@@ -24,7 +24,7 @@ EXPORTS = ["bwta_plane_row_words", "bwta_workspace_bytes", "bwta_quantize_pack_a
            "bwta_pack_weights", "bwta_gemm", "bwta_linear", "bwta_strerror", "bwta_last_hip_error",
            "bwta_set_path", "bwta_get_path", "bwta_auto_path", "bwta_version", "bwta_set_tile",
            "bwta_prepared_bytes", "bwta_prepare_act", "bwta_gemm_prepared", "bwta_gemm_grouped",
-           "bwta_quantize_pack_bool", "bwta_matmul_tt"]
+           "bwta_quantize_pack_bool", "bwta_matmul_tt", "bwta_prepare_weights", "bwta_act_scale"]
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -70,6 +70,10 @@ _lib.bwta_quantize_pack_bool.argtypes = [_P, _c.c_int64, _P, _c.c_int, _c.c_int,
 _lib.bwta_matmul_tt.restype = _c.c_int
 _lib.bwta_matmul_tt.argtypes = [_P, _P, _c.c_int64, _P, _P, _c.c_int64, _c.c_int, _c.c_int, _c.c_int, _c.c_int,
                                 _P, _c.c_int, _P, _c.c_int, _c.c_float, _P, _P, _c.c_int64, _c.c_int64, _P]
+_lib.bwta_prepare_weights.restype = _c.c_int
+_lib.bwta_prepare_weights.argtypes = [_P, _c.c_int64, _c.c_int, _c.c_int, _P, _P, _P]
+_lib.bwta_act_scale.restype = _c.c_int
+_lib.bwta_act_scale.argtypes = [_P, _c.c_int64, _c.c_int, _c.c_int, _P, _P]
 _lib.bwta_strerror.restype = _c.c_char_p
 _lib.bwta_strerror.argtypes = [_c.c_int]
 _lib.bwta_last_hip_error.restype = _c.c_int
@@ -206,6 +210,16 @@ def bwta_matmul_tt(maskA, signA, maskB, signB, s_a, s_b, acc, out, *, batch, M, 
     _check(_lib.bwta_matmul_tt(_ptr(maskA), _ptr(signA), strideA, _ptr(maskB), _ptr(signB), strideB, batch, M, N, K,
                                _ptr(s_a), _mode(s_a, a_scale_mode), _ptr(s_b), _mode(s_b, b_scale_mode), float(alpha),
                                _ptr(acc), _ptr(out), ldo, stride_out, _stream(stream)))
+
+
+def bwta_prepare_weights(W, wsign, s_w, *, N, K, ldw=None, stream=None):
+    ldw = K if ldw is None else ldw
+    _check(_lib.bwta_prepare_weights(_ptr(W), ldw, N, K, _ptr(wsign), _ptr(s_w), _stream(stream)))
+
+
+def bwta_act_scale(A, s, *, M, K, lda=None, stream=None):
+    lda = K if lda is None else lda
+    _check(_lib.bwta_act_scale(_ptr(A), lda, M, K, _ptr(s), _stream(stream)))
 
 
 def _nbytes(buf, given):

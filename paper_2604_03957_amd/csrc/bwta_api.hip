@@ -297,6 +297,29 @@ int bwta_matmul_tt(const uint32_t *maskA, const uint32_t *signA, int64_t strideA
     return hip_result(bwta::launch_matmul_tt(g, (hipStream_t)stream));
 }
 
+int bwta_prepare_weights(const void *W, int64_t ldw, int N, int K, uint32_t *wsign, void *s_w,
+                         bwta_stream_t stream)
+{
+    if (N < 0 || K < 0 || (N > 0 && K == 0)) return BWTA_ERR_SHAPE;
+    if (N == 0) return BWTA_OK;
+    if (ldw < K) return BWTA_ERR_SHAPE;
+    if (K > 32768) return BWTA_ERR_UNSUPPORTED;  // K * value must stay inside 64 bits
+    if (!W || !wsign || !s_w) return BWTA_ERR_NULL;
+    if (!aligned(wsign, 16) || !aligned(W, 2) || !aligned(s_w, 2)) return BWTA_ERR_ALIGN;
+    return hip_result(bwta::launch_prepare_weights(W, ldw, N, K, wsign, (uint16_t *)s_w, (hipStream_t)stream));
+}
+
+int bwta_act_scale(const void *A, int64_t lda, int M, int K, void *s, bwta_stream_t stream)
+{
+    if (M < 0 || K < 0 || (M > 0 && K == 0)) return BWTA_ERR_SHAPE;
+    if (M == 0) return BWTA_OK;
+    if (lda < K) return BWTA_ERR_SHAPE;
+    if (K > 32768) return BWTA_ERR_UNSUPPORTED;
+    if (!A || !s) return BWTA_ERR_NULL;
+    if (!aligned(A, 2) || !aligned(s, 2)) return BWTA_ERR_ALIGN;
+    return hip_result(bwta::launch_act_scale(A, lda, M, K, (uint16_t *)s, (hipStream_t)stream));
+}
+
 const char *bwta_strerror(int code)
 {
     switch (code) {

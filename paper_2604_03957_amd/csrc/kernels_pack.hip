@@ -162,7 +162,163 @@ __global__ __launch_bounds__(kThreads) void k_row_popcount(const uint32_t *__res
     if (lane == 0) nnz[m] = c;
 }
 
+// ---- weight preparation from full-precision weights, and the activation scale's starting value ----
+//
+// Binary16 values are integers in units of 2^-24 (|v| < 2^40), so a row's sum is an exact 64-bit
+// integer whatever the order of the additions, and "W[n,k] - mean >= 0" is the integer test
+// K * W[n,k] >= sum.  Every discrete decision is therefore identical to exact arithmetic.
+
+// finite binary16 -> integer count of 2^-24; NaN / Inf -> 0 with *finite = false
+__device__ __forceinline__ long long half_fixed(uint16_t h, bool *finite)
+{
+    const int expo = (h >> 10) & 0x1f, frac = h & 0x3ff;
+    *finite = expo != 31;
+    long long v = expo == 0 ? (long long)frac : ((long long)(1024 + frac) << (expo - 1));
+    if (expo == 31) v = 0;
+    return (h & 0x8000) ? -v : v;
+}
+
+// non-negative double -> binary16 bits, round to nearest even, straight from the 53-bit significand
+// (going through fp32 would round twice)
+__device__ __forceinline__ uint16_t double_to_half_bits(double x)
+{
+    if (!(x > 0.0)) return 0;
+    const unsigned long long b = (unsigned long long)__double_as_longlong(x);
+    int e = (int)((b >> 52) & 0x7ff) - 1023;
+    if (e > 15) return 0x7c00;
+    if (e < -26) return 0;  // below half of the smallest subnormal
+    const unsigned long long mant = (b & ((1ull << 52) - 1)) | (1ull << 52);
+    const int shift = 42 + (e < -14 ? -14 - e : 0);  // bits dropped: keep 11 (normal) or fewer (subnormal)
+    unsigned long long q = mant >> shift;
+    const unsigned long long rem = mant & ((1ull << shift) - 1), half = 1ull << (shift - 1);
+    if (rem > half || (rem == half && (q & 1))) ++q;
+    if (e < -14) return (uint16_t)q;  // subnormal, or exactly the smallest normal (q = 1024)
+    if (q == 2048) {
+        q = 1024;
+        ++e;
+    }
+    if (e > 15) return 0x7c00;
+    return (uint16_t)(((e + 15) << 10) | (int)(q - 1024));
+}
+
+template <typename T>
+__device__ __forceinline__ T block_sum(T v, T *scratch /* [kThreads / 64] */)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    __syncthreads();  // scratch may still be read from a previous call
+    if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
+    __syncthreads();
+    T r = scratch[0];
+#pragma unroll
+    for (int i = 1; i < kThreads / 64; ++i) r += scratch[i];
+    return r;
+}
+
+__device__ __forceinline__ void load8_halfs(const uint16_t *row, int k0, int nvalid, bool vec_ok, uint16_t v[8])
+{
+    if (nvalid == 8 && vec_ok) {
+        const uint4 q = *(const uint4 *)(row + k0);
+        v[0] = q.x & 0xffff; v[1] = q.x >> 16; v[2] = q.y & 0xffff; v[3] = q.y >> 16;
+        v[4] = q.z & 0xffff; v[5] = q.z >> 16; v[6] = q.w & 0xffff; v[7] = q.w >> 16;
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = i < nvalid ? row[k0 + i] : (uint16_t)0;
+    }
+}
+
+// One workgroup per output channel: mean (exact), sign(W - mean) packed like bwta_pack_weights,
+// s_w = mean |W - mean| (sum of exact integers |K W - sum| in double, one division, one rounding).
+__global__ __launch_bounds__(kThreads) void k_prepare_weights(const uint16_t *__restrict__ W, int64_t ldw, int K,
+                                                              int rw, uint32_t *__restrict__ wsign,
+                                                              uint16_t *__restrict__ s_w, int vec_ok)
+{
+    __shared__ long long s_ll[kThreads / 64];
+    __shared__ double s_d[kThreads / 64];
+    const int n = blockIdx.x, c8 = rw * 4, lane = threadIdx.x & 63;
+    const uint16_t *row = W + (int64_t)n * ldw;
+    long long part = 0;
+    for (int c = threadIdx.x; c < c8; c += kThreads) {
+        const int k0 = c * 8, nvalid = K - k0 >= 8 ? 8 : (K - k0 > 0 ? K - k0 : 0);
+        uint16_t v[8];
+        load8_halfs(row, k0, nvalid, vec_ok, v);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            bool fin;
+            part += half_fixed(v[i], &fin);  // padding reads as +0
+        }
+    }
+    const long long S = block_sum(part, s_ll);
+    double tpart = 0.0;
+    for (int c0 = 0; c0 < c8; c0 += kThreads) {  // whole quads stay together for quad_word
+        const int c = c0 + threadIdx.x;
+        uint32_t bits = 0;
+        if (c < c8) {
+            const int k0 = c * 8, nvalid = K - k0 >= 8 ? 8 : (K - k0 > 0 ? K - k0 : 0);
+            uint16_t v[8];
+            load8_halfs(row, k0, nvalid, vec_ok, v);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                bool fin;
+                const long long x = half_fixed(v[i], &fin);
+                const long long d = x * K - S;  // |x K| < 2^40 * 2^15
+                const bool neg = fin ? d < 0 : v[i] != 0x7c00;  // -Inf and NaN -> -1, +Inf -> +1
+                if (i < nvalid) {
+                    bits |= (uint32_t)neg << i;
+                    if (fin) tpart += (double)(d < 0 ? -d : d);
+                }
+            }
+        }
+        const uint32_t word = quad_word(bits, lane);
+        if (c < c8 && (lane & 3) == 0) wsign[(int64_t)n * rw + (c >> 2)] = word;
+    }
+    const double T = block_sum(tpart, s_d);
+    if (threadIdx.x == 0) s_w[n] = double_to_half_bits(T / ((double)K * (double)K * 16777216.0));
+}
+
+// One workgroup per token: s[m] = 2 * mean_k |A[m, k]| (exact integer sum, one division, one rounding).
+__global__ __launch_bounds__(kThreads) void k_act_scale(const uint16_t *__restrict__ A, int64_t lda, int K,
+                                                        uint16_t *__restrict__ s, int vec_ok)
+{
+    __shared__ long long s_ll[kThreads / 64];
+    const int m = blockIdx.x, c8 = (K + 7) / 8;
+    const uint16_t *row = A + (int64_t)m * lda;
+    long long part = 0;
+    for (int c = threadIdx.x; c < c8; c += kThreads) {
+        const int k0 = c * 8, nvalid = K - k0 >= 8 ? 8 : K - k0;
+        uint16_t v[8];
+        load8_halfs(row, k0, nvalid, vec_ok, v);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            bool fin;
+            const long long x = half_fixed(v[i], &fin);
+            part += x < 0 ? -x : x;
+        }
+    }
+    const long long S = block_sum(part, s_ll);
+    if (threadIdx.x == 0) s[m] = double_to_half_bits((double)S / ((double)K * 8388608.0));  // 2 S / (K 2^24)
+}
+
 }  // namespace
+
+hipError_t launch_prepare_weights(const void *W, int64_t ldw, int N, int K, uint32_t *wsign, uint16_t *s_w,
+                                  hipStream_t st)
+{
+    if (N == 0) return hipSuccess;
+    const int rw = 4 * ((K + 127) / 128);
+    const int vec_ok = (((uintptr_t)W % 16) == 0 && (ldw % 8) == 0) ? 1 : 0;
+    hipLaunchKernelGGL(k_prepare_weights, dim3(N), dim3(kThreads), 0, st, (const uint16_t *)W, ldw, K, rw, wsign, s_w,
+                       vec_ok);
+    return hipGetLastError();
+}
+
+hipError_t launch_act_scale(const void *A, int64_t lda, int M, int K, uint16_t *s, hipStream_t st)
+{
+    if (M == 0) return hipSuccess;
+    const int vec_ok = (((uintptr_t)A % 16) == 0 && (lda % 8) == 0) ? 1 : 0;
+    hipLaunchKernelGGL(k_act_scale, dim3(M), dim3(kThreads), 0, st, (const uint16_t *)A, lda, K, s, vec_ok);
+    return hipGetLastError();
+}
 
 hipError_t launch_quantize_pack(const void *A, int dtype, int64_t lda, ScaleArg s_a, int M, int K,
                                 uint32_t *mask, uint32_t *sign, int32_t *nnz, hipStream_t st)

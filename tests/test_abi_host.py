@@ -130,3 +130,21 @@ def test_attention_entry_points_reject_bad_arguments():
     assert _code(mm, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, FAKE, **dict(kw, alpha=float("inf"))) == B.ERR_UNSUPPORTED
     assert _code(mm, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, FAKE, **dict(kw, batch=-1)) == B.ERR_SHAPE
     mm(FAKE, FAKE, FAKE, FAKE, None, None, FAKE, FAKE, **dict(kw, batch=0))  # empty batch: nothing enqueued
+
+
+def test_weight_preparation_entry_points_reject_bad_arguments():
+    pw = B.bwta_prepare_weights
+    kw = dict(N=4, K=256, stream=0)
+    assert _code(pw, None, FAKE, FAKE, **kw) == B.ERR_NULL
+    assert _code(pw, FAKE, FAKE, None, **kw) == B.ERR_NULL
+    assert _code(pw, FAKE, FAKE + 4, FAKE, **kw) == B.ERR_ALIGN
+    assert _code(pw, FAKE, FAKE, FAKE, **dict(kw, ldw=255)) == B.ERR_SHAPE
+    assert _code(pw, FAKE, FAKE, FAKE, **dict(kw, K=32769)) == B.ERR_UNSUPPORTED
+    pw(FAKE, FAKE, FAKE, **dict(kw, N=0))
+    sc = B.bwta_act_scale
+    kw = dict(M=4, K=256, stream=0)
+    assert _code(sc, None, FAKE, **kw) == B.ERR_NULL
+    assert _code(sc, FAKE, FAKE + 1, **kw) == B.ERR_ALIGN
+    assert _code(sc, FAKE, FAKE, **dict(kw, lda=8)) == B.ERR_SHAPE
+    assert _code(sc, FAKE, FAKE, **dict(kw, K=40000)) == B.ERR_UNSUPPORTED
+    sc(FAKE, FAKE, **dict(kw, M=0))

@@ -371,3 +371,83 @@ def test_epilogue_alpha_against_exact_rational_arithmetic():
             assert got[m, n].view(np.uint16) == want.view(np.uint16), (m, n)
     # alpha = 1 reduces to the linear layer's epilogue
     assert np.array_equal(oracle.epilogue_alpha(acc, s_a, s_b, 1.0).view(np.uint16), oracle.epilogue(acc, s_a, s_b).view(np.uint16))
+
+
+# ---- weight preparation and the activation scale's starting value --------------------------
+
+def _exact_prepare(row):
+    vals = [Fraction(float(x)) for x in row]
+    mu = sum(vals) / len(vals)
+    w = [1 if v - mu >= 0 else -1 for v in vals]
+    s = sum(abs(v - mu) for v in vals) / len(vals)
+    return w, s
+
+
+def _half_of_fraction(q):
+    """Correctly rounded binary16 of a non-negative rational, by bisection over all finite halfs."""
+    halfs = np.arange(0, 0x7c00, dtype=np.uint16).view(np.float16)            # ascending
+    fr = [Fraction(float(h)) for h in (halfs[0], halfs[-1])]
+    lo, hi = 0, len(halfs) - 1
+    if q >= fr[1]:
+        return halfs[-1]
+    while hi - lo > 1:
+        mid = (lo + hi) // 2
+        if Fraction(float(halfs[mid])) <= q:
+            lo = mid
+        else:
+            hi = mid
+    a, b = Fraction(float(halfs[lo])), Fraction(float(halfs[hi]))
+    if q - a < b - q or (q - a == b - q and lo % 2 == 0):
+        return halfs[lo]
+    return halfs[hi]
+
+
+def test_prepare_weights_against_exact_rational_arithmetic():
+    W = (synth.gaussian(41, 1, 6 * 37) * 0.05 + 0.01).astype(np.float16).reshape(6, 37)
+    W[0, :3] = [0.25, 0.25, 0.25]
+    W[1] = np.float16(0.125)                         # every element equals the mean: all +1, scale 0
+    W[2, :4] = [6e-8, -6e-8, 65504.0, -65504.0]      # subnormals and the largest finite values
+    w, s = oracle.prepare_weights(W)
+    for n in range(W.shape[0]):
+        we, se = _exact_prepare(W[n])
+        assert w[n].tolist() == we, n
+        assert s[n].view(np.uint16) == _half_of_fraction(se).view(np.uint16), n
+    assert w[1].tolist() == [1] * 37 and s[1] == 0
+
+
+def test_prepare_weights_scale_is_the_least_squares_optimum():
+    W = (synth.laplace(42, 1, 3 * 64) * 0.02).astype(np.float16).reshape(3, 64)
+    w, s = oracle.prepare_weights(W)
+    for n in range(3):
+        vals = [Fraction(float(x)) for x in W[n]]
+        mu = sum(vals) / len(vals)
+        c = [v - mu for v in vals]
+        err = lambda sc: sum((ci - sc * wi) ** 2 for ci, wi in zip(c, w[n].tolist()))
+        s_opt = sum(abs(ci) for ci in c) / len(c)                # d/ds of the error vanishes here
+        assert err(s_opt) <= err(s_opt * Fraction(1001, 1000)) and err(s_opt) <= err(s_opt * Fraction(999, 1000))
+        assert abs(Fraction(float(s[n])) - s_opt) <= s_opt * Fraction(1, 2048)   # one rounding to binary16
+        assert sum(w[n].tolist()) != 64                          # centred weights are not all of one sign
+
+
+def test_prepare_weights_matches_float64_numpy_and_special_values():
+    W = (synth.gaussian(43, 1, 40 * 768) * 0.03 + 0.004).astype(np.float16).reshape(40, 768)
+    w, s = oracle.prepare_weights(W)
+    W64 = W.astype(np.float64)
+    c = W64 - W64.mean(axis=1, keepdims=True)
+    assert np.array_equal(w, np.where(c >= 0, 1, -1))            # no element sits within rounding of its row mean
+    ref = np.abs(c).mean(axis=1)
+    assert np.all(np.abs(s.astype(np.float64) - ref) <= ref * 2.0 ** -11)
+    V = np.array([[1.0, np.inf, -np.inf, np.nan, -1.0, 3.0]], np.float16)
+    w, s = oracle.prepare_weights(V)                             # finite part: {1, -1, 3}, sum 3 over K = 6 -> mean 0.5
+    assert w.tolist() == [[1, 1, -1, -1, -1, 1]]
+    assert s[0] == np.float16((0.5 + 1.5 + 2.5) / 6)
+
+
+def test_act_scale_is_twice_the_mean_absolute_value():
+    c = synth.config2("up", M=16)
+    got = oracle.act_scale(c["A"])
+    assert np.array_equal(got.view(np.uint16), c["s_a"].view(np.uint16))      # the input recipe computes it in float64
+    A = np.array([[1.0, -2.0, 0.5, 0.0], [6e-8, 6e-8, 0.0, 0.0], [65504.0] * 4], np.float16)
+    with np.errstate(over="ignore"):
+        want = [np.float16(1.75), _half_of_fraction(Fraction(float(np.float16(6e-8))) * 2 * 2 / 4), np.float16(np.inf)]
+    assert [x.view(np.uint16) for x in oracle.act_scale(A)] == [x.view(np.uint16) for x in want]
