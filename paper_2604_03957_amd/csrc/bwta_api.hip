@@ -122,12 +122,17 @@ int bwta_gemm(const uint32_t *mask, const uint32_t *sign, const uint32_t *wsign,
     int rc = check_gemm_common(M, N, K, s_a, a_scale_mode, s_w, w_scale_mode, out, ldo);
     if (rc != BWTA_OK) return rc;
     if (M == 0 || N == 0) return BWTA_OK;
-    if (!mask || !sign || !wsign) return BWTA_ERR_NULL;
+    if (!sign || !wsign) return BWTA_ERR_NULL;
     if (!acc && !out) return BWTA_ERR_NULL;
-    if (!aligned(mask, 16) || !aligned(sign, 16) || !aligned(wsign, 16)) return BWTA_ERR_ALIGN;
+    if ((mask && !aligned(mask, 16)) || !aligned(sign, 16) || !aligned(wsign, 16)) return BWTA_ERR_ALIGN;
     if (acc && !aligned(acc, 4)) return BWTA_ERR_ALIGN;
     if (!workspace || workspace_bytes < bwta_workspace_bytes(M, N, K)) return BWTA_ERR_WORKSPACE;
     if (!aligned(workspace, 256)) return BWTA_ERR_ALIGN;
+    if (!mask) {  // binary (+-1) activations: the W1A1 layer.  Every element is non-zero.
+        int rcm = hip_result(bwta::launch_full_mask((uint32_t *)workspace, M, K, (hipStream_t)stream));
+        if (rcm != BWTA_OK) return rcm;
+        mask = (const uint32_t *)workspace;  // the mask area of the workspace is otherwise unused here
+    }
     bwta::GemmArgs g{mask, sign, wsign, M, N, K, (int)bwta_plane_row_words(K),
                      {(const uint16_t *)s_a, s_a ? a_scale_mode : BWTA_SCALE_NONE},
                      {(const uint16_t *)s_w, s_w ? w_scale_mode : BWTA_SCALE_NONE},

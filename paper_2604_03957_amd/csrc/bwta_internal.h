@@ -36,6 +36,7 @@ struct MatmulTTArgs {
 hipError_t launch_matmul_tt(const MatmulTTArgs &g, hipStream_t st);
 hipError_t launch_prepare_weights(const void *W, int64_t ldw, int N, int K, uint32_t *wsign, uint16_t *s_w,
                                   hipStream_t st);
+hipError_t launch_full_mask(uint32_t *mask, int M, int K, hipStream_t st);
 hipError_t launch_act_scale(const void *A, int64_t lda, int M, int K, uint16_t *s, hipStream_t st);
 hipError_t launch_quantize_pack_bool(const void *A, int64_t lda, ScaleArg s_a, int M, int K, uint32_t *mask,
                                      hipStream_t st);

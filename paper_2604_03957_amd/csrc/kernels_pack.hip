@@ -299,7 +299,26 @@ __global__ __launch_bounds__(kThreads) void k_act_scale(const uint16_t *__restri
     if (threadIdx.x == 0) s[m] = double_to_half_bits((double)S / ((double)K * 8388608.0));  // 2 S / (K 2^24)
 }
 
+// mask plane of a binary (+-1) activation matrix: every element is non-zero; pad bits stay zero
+__global__ __launch_bounds__(kThreads) void k_full_mask(uint32_t *__restrict__ mask, int64_t words, int rw, int K)
+{
+    const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (gid >= words) return;
+    const int q = (int)(gid % rw), left = K - 32 * q;
+    mask[gid] = left >= 32 ? 0xffffffffu : (left > 0 ? (1u << left) - 1u : 0u);
+}
+
 }  // namespace
+
+hipError_t launch_full_mask(uint32_t *mask, int M, int K, hipStream_t st)
+{
+    const int rw = 4 * ((K + 127) / 128);
+    const int64_t words = (int64_t)M * rw;
+    if (words == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_full_mask, dim3((unsigned)((words + kThreads - 1) / kThreads)), dim3(kThreads), 0, st, mask,
+                       words, rw, K);
+    return hipGetLastError();
+}
 
 hipError_t launch_prepare_weights(const void *W, int64_t ldw, int N, int K, uint32_t *wsign, uint16_t *s_w,
                                   hipStream_t st)

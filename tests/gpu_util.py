@@ -57,7 +57,7 @@ def gpu_pack_weights(W, K=None):
 
 def gpu_gemm(mask, sign, wsign, s_a, s_w, M, N, K, path=B.PATH_AUTO, want_acc=True, want_out=True):
     """Planes may be numpy or device tensors.  Returns (acc int32 numpy, out fp16 numpy)."""
-    dm = mask if torch.is_tensor(mask) else dev(mask)
+    dm = mask if torch.is_tensor(mask) or mask is None else dev(mask)
     dsg = sign if torch.is_tensor(sign) else dev(sign)
     dw = wsign if torch.is_tensor(wsign) else dev(wsign)
     acc = torch.full((M, N), 123456, dtype=torch.int32, device=DEV) if want_acc else None

@@ -79,7 +79,7 @@ def test_gemm_and_linear_reject_bad_arguments():
     ws = B.workspace_bytes(8, 8, 128)
     kw = dict(M=8, N=8, K=128, stream=0, workspace_bytes=ws, a_scale_mode=B.SCALE_VECTOR,
               w_scale_mode=B.SCALE_VECTOR)
-    assert _code(g, None, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, **kw) == B.ERR_NULL
+    assert _code(g, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, **kw) == B.ERR_NULL   # a NULL mask alone is legal (binary activations)
     assert _code(g, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, **kw) == B.ERR_NULL   # no output at all
     assert _code(g, FAKE, FAKE, FAKE + 4, FAKE, FAKE, FAKE, FAKE, FAKE, **kw) == B.ERR_ALIGN
     assert _code(g, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, **dict(kw, ldo=7)) == B.ERR_SHAPE

@@ -339,3 +339,21 @@ def test_gemm_grouped_matches_oracle(M, N, K, count, path):
     for (dw, dsw, acc, out), (acc_want, out_want) in zip(keep, want):
         assert np.array_equal(acc.cpu().numpy(), acc_want)
         assert same_half(out.cpu().numpy(), out_want)
+
+
+@pytest.mark.parametrize("path", [B.PATH_AUTO] + PATHS)
+@pytest.mark.parametrize("M,N,K", [(64, 96, 768), (3, 130, 1000), (130, 70, 129), (16, 257, 4096)])
+def test_binary_activations_w1a1(M, N, K, path):
+    """mask == NULL: binary (+-1) activations, the W1A1 "Binary Linear" special case
+    acc = K - 2 popc(x ^ w); the activation signs are packed with the sign packer."""
+    _say("w1a1", M, N, K, path)
+    x = synth.binary_pm1(4000 + M, 1, (M, K))
+    w = synth.binary_pm1(4000 + M, 2, (N, K))
+    s_a, s_w = synth.scales(4000, 3, M), synth.scales(4000, 4, N)
+    want_acc = oracle.gemm_unpacked(x, w)
+    xs, wsn = oracle.pack_weights(x), oracle.pack_weights(w)
+    xor_popc = np.array([[bin(int.from_bytes((xs[m] ^ wsn[n]).tobytes(), "little")).count("1") for n in range(N)] for m in range(min(M, 4))])
+    assert np.array_equal(want_acc[:min(M, 4)], K - 2 * xor_popc)           # the textbook XNOR-popcount form
+    acc, out = gpu_gemm(None, xs, wsn, s_a, s_w, M, N, K, path=path)
+    assert np.array_equal(acc, want_acc)
+    assert same_half(out, oracle.epilogue(want_acc, s_a, s_w))
