@@ -83,53 +83,73 @@ __global__ __launch_bounds__(256) void k_planes_to_fp4(const uint32_t *__restric
 // elements (one 128-bit load); the 4 lanes of a quad cover one 32-element word, whose 4 nibble
 // dwords are assembled with a byte transpose inside the quad.  Quads of a wavefront walk
 // consecutive rows, so the 16-byte fragments they store are contiguous.
+// QF_R: k steps (2 plane words) per thread; more than one amortises constants and addressing when
+// the launch still has enough workgroups to fill the chip.
+template <int QF_R>
 __global__ __launch_bounds__(256) void k_quantize_to_fp4(const uint16_t *__restrict__ A, int64_t lda, ScaleArg s_a,
                                                          int M, int K, int s_pad, uint32_t *__restrict__ frag,
                                                          int vec_ok)
 {
-    const int t = threadIdx.x, lane = t & 63;
+    const int t = threadIdx.x;
     const int quad = t >> 2, j = t & 3;
-    const int row = quad & 31, q = 2 * blockIdx.x + (quad >> 5);  // row in block, plane word index
+    const int row = quad & 31;  // row in block
     const int rb = blockIdx.y, m = rb * 32 + row;
-    const int k0 = 32 * q + 8 * j;
-    uint32_t V = 0;  // byte d = nibbles of elements d (low) and d + 4 (high): mask -> bit 1, sign -> bit 3
-    if (m < M && k0 < K) {
-        const uint16_t *src = A + (int64_t)m * lda + k0;
-        const int nvalid = K - k0 >= 8 ? 8 : K - k0;
-        uint16_t v[8];
-        if (nvalid == 8 && vec_ok) {
-            const uint4 x = *(const uint4 *)src;
-            v[0] = x.x & 0xffff; v[1] = x.x >> 16; v[2] = x.y & 0xffff; v[3] = x.y >> 16;
-            v[4] = x.z & 0xffff; v[5] = x.z >> 16; v[6] = x.w & 0xffff; v[7] = x.w >> 16;
-        } else {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = e < nvalid ? src[e] : (uint16_t)0;
-        }
+    const int q0 = 2 * QF_R * blockIdx.x + (quad >> 5);  // first plane word of this quad; then every second one
+
+    // thresholds: 0.5 s is exact.  An invalid scale turns them into NaN, against which every compare
+    // fails; elements past K are loaded as +0 and fail both compares as well, so the element loop
+    // needs no validity logic: convert, two compares, two selects, one shift-or.
+    float hthr = __builtin_nanf("");
+    if (m < M) {
         const float s = load_scale(s_a, m);
-        const bool ok = (s > 0.0f) && (s < __builtin_inff());
-        const float hthr = 0.5f * s;  // exact
+        if ((s > 0.0f) && (s < __builtin_inff())) hthr = 0.5f * s;
+    }
+    const float nthr = -hthr;
+
+    uint4 x[QF_R];  // all of the thread's loads are issued before the first is used
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float a = half_bits_to_float(v[e]);
-            const bool pos = a >= hthr, neg = a < -hthr;  // NaN fails both; pads are +0
-            const bool live = ok && e < nvalid;
-            const int base = 8 * (e & 3) + 4 * (e >> 2);
-            V |= (uint32_t)(live && (pos || neg)) << (base + 1);
-            V |= (uint32_t)(live && neg) << (base + 3);
+    for (int it = 0; it < QF_R; ++it) {
+        const int k0 = 32 * (q0 + 2 * it) + 8 * j;
+        x[it] = make_uint4(0, 0, 0, 0);
+        if (m < M && k0 < K) {
+            const uint16_t *src = A + (int64_t)m * lda + k0;
+            const int nvalid = K - k0 >= 8 ? 8 : K - k0;
+            if (nvalid == 8 && vec_ok) {
+                x[it] = *(const uint4 *)src;
+            } else {
+                uint16_t v[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = e < nvalid ? src[e] : (uint16_t)0;
+                x[it] = make_uint4(v[0] | ((uint32_t)v[1] << 16), v[2] | ((uint32_t)v[3] << 16),
+                                   v[4] | ((uint32_t)v[5] << 16), v[6] | ((uint32_t)v[7] << 16));
+            }
         }
     }
-    // quad byte transpose: lane d of the quad collects byte d of every lane -> dword d of the word
-    const uint32_t x0 = __builtin_amdgcn_mov_dpp(V, 0x00, 0xf, 0xf, true);  // quad_perm [0,0,0,0]
-    const uint32_t x1 = __builtin_amdgcn_mov_dpp(V, 0x55, 0xf, 0xf, true);  // [1,1,1,1]
-    const uint32_t x2 = __builtin_amdgcn_mov_dpp(V, 0xaa, 0xf, 0xf, true);  // [2,2,2,2]
-    const uint32_t x3 = __builtin_amdgcn_mov_dpp(V, 0xff, 0xf, 0xf, true);  // [3,3,3,3]
-    const uint32_t sh = 8 * j;
-    const uint32_t D = ((x0 >> sh) & 0xffu) | (((x1 >> sh) & 0xffu) << 8) | (((x2 >> sh) & 0xffu) << 16) |
-                       (((x3 >> sh) & 0xffu) << 24);
-    (void)lane;
-    int step, half;
-    word_slot(q, step, half);
-    if (step < s_pad) frag[(((int64_t)rb * s_pad + step) * 64 + half * 32 + row) * 4 + j] = D;
+#pragma unroll
+    for (int it = 0; it < QF_R; ++it) {
+        const int q = q0 + 2 * it;
+        const uint32_t w[4] = {x[it].x, x[it].y, x[it].z, x[it].w};
+        uint32_t V = 0;  // byte d = nibbles of elements d (low) and d + 4 (high): mask -> bit 1, sign -> bit 3
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float a = half_bits_to_float((uint16_t)(w[e >> 1] >> (16 * (e & 1))));
+            uint32_t sel = a >= hthr ? 1u : 0u;  // mask bit; NaN fails both compares
+            sel = a < nthr ? 5u : sel;           // mask bit and, two places up, the sign bit
+            const int base = 8 * (e & 3) + 4 * (e >> 2);
+            V = (sel << (base + 1)) | V;
+        }
+        // quad byte transpose: lane d of the quad collects byte d of every lane -> dword d of the word
+        const uint32_t x0 = __builtin_amdgcn_mov_dpp(V, 0x00, 0xf, 0xf, true);  // quad_perm [0,0,0,0]
+        const uint32_t x1 = __builtin_amdgcn_mov_dpp(V, 0x55, 0xf, 0xf, true);  // [1,1,1,1]
+        const uint32_t x2 = __builtin_amdgcn_mov_dpp(V, 0xaa, 0xf, 0xf, true);  // [2,2,2,2]
+        const uint32_t x3 = __builtin_amdgcn_mov_dpp(V, 0xff, 0xf, 0xf, true);  // [3,3,3,3]
+        const uint32_t sh = 8 * j;
+        const uint32_t D = ((x0 >> sh) & 0xffu) | (((x1 >> sh) & 0xffu) << 8) | (((x2 >> sh) & 0xffu) << 16) |
+                           (((x3 >> sh) & 0xffu) << 24);
+        int step, half;
+        word_slot(q, step, half);
+        if (step < s_pad) frag[(((int64_t)rb * s_pad + step) * 64 + half * 32 + row) * 4 + j] = D;
+    }
 }
 
 // weight bits -> E2M1 nibbles (+1 = 0b0010, -1 = 0b1010): element 4 i + d -> nibble i of dword d.
@@ -480,8 +500,16 @@ hipError_t launch_quantize_to_fp4(const void *A, int64_t lda, ScaleArg s_a, int 
     const int rw = 4 * ((K + 127) / 128);
     const int rb_pad = fp4_rb_pad(M), s_pad = fp4_s_pad(rw);
     const int vec_ok = (((uintptr_t)A % 16) == 0 && (lda % 8) == 0) ? 1 : 0;
-    hipLaunchKernelGGL(k_quantize_to_fp4, dim3(s_pad, rb_pad), dim3(256), 0, st, (const uint16_t *)A, lda, s_a, M, K,
-                       s_pad, frag, vec_ok);
+    const int64_t units = (int64_t)s_pad * rb_pad;  // workgroups at one k step per thread
+    if (units >= 4 * 2048)
+        hipLaunchKernelGGL(k_quantize_to_fp4<4>, dim3((s_pad + 3) / 4, rb_pad), dim3(256), 0, st, (const uint16_t *)A, lda,
+                           s_a, M, K, s_pad, frag, vec_ok);
+    else if (units >= 2 * 2048)
+        hipLaunchKernelGGL(k_quantize_to_fp4<2>, dim3((s_pad + 1) / 2, rb_pad), dim3(256), 0, st, (const uint16_t *)A, lda,
+                           s_a, M, K, s_pad, frag, vec_ok);
+    else
+        hipLaunchKernelGGL(k_quantize_to_fp4<1>, dim3(s_pad, rb_pad), dim3(256), 0, st, (const uint16_t *)A, lda, s_a, M,
+                           K, s_pad, frag, vec_ok);
     return hipGetLastError();
 }
 

@@ -27,14 +27,20 @@ struct TernaryBits {
 __device__ __forceinline__ TernaryBits ternary_bits_fp16(const uint16_t v[8], int nvalid, float h, bool ok)
 {
     TernaryBits r{0u, 0u};
+    // an invalid scale becomes a NaN threshold (every compare fails); elements past nvalid were
+    // loaded as +0 and fail both compares too, h being positive
+    (void)nvalid;
+    const float hp = ok ? h : __builtin_nanf(""), hn = -hp;
+    uint32_t both = 0;  // bits 0..7 non-zero flags, bits 8..15 negative flags
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        float a = half_bits_to_float(v[i]);
-        bool pos = a >= h, neg = a < -h;  // NaN fails both
-        bool live = ok && (i < nvalid);
-        r.nz |= (uint32_t)(live && (pos || neg)) << i;
-        r.neg |= (uint32_t)(live && neg) << i;
+        const float a = half_bits_to_float(v[i]);
+        uint32_t sel = a >= hp ? 1u : 0u;  // NaN fails both compares
+        sel = a < hn ? 0x101u : sel;
+        both = (sel << i) | both;
     }
+    r.nz = both & 0xffu;
+    r.neg = both >> 8;
     return r;
 }
 
