@@ -355,7 +355,7 @@ int bwta_auto_path(int M, int N, int K)
     (void)N;
     (void)K;
     // one or two tokens: the popcount decode kernel; more: the FP4 matrix cores (decode kernel up to
-    // 16 tokens, tiled kernel above)
+    // 64 tokens, tiled kernel above)
     return M > 2 ? BWTA_PATH_FP4 : BWTA_PATH_POPC;
 }
 

@@ -44,7 +44,7 @@ struct DecodeBatch {
 };
 
 struct DecodeShape {
-    int M, N, rw, a_mode, w_mode;
+    int M, N, rw, a_mode, w_mode;  // M tokens in all; grid.z walks them in groups of 16
     int P;  // 16-byte pieces per packed row (rw / 4)
     int64_t ldo;
 };
@@ -59,6 +59,8 @@ __global__ __launch_bounds__(64 * MAXW) void k_gemv_fp4(DecodeBatch b, DecodeSha
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, KW = blockDim.x >> 6;
     const int i = lane & 15, g = lane >> 4;
     const int p = blockIdx.y;
+    const int tok0 = 16 * blockIdx.z;                                 // first token of this group
+    const int Mg = sh.M - tok0 < 16 ? sh.M - tok0 : 16;               // tokens in it
     const int rw = sh.rw, P = sh.P;
     const int64_t tile0 = (int64_t)blockIdx.x * T;
     const uint32_t *wsign = b.wsign[p];
@@ -74,12 +76,12 @@ __global__ __launch_bounds__(64 * MAXW) void k_gemv_fp4(DecodeBatch b, DecodeSha
     // token operand is zero, so whatever the weight operand holds there adds nothing.
     uint4 m4[RPW], s4[RPW];
     {
-        const uint32_t *mask = b.mask[p], *sign = b.sign[p];
-        const int tk = i < sh.M ? i : 0;
+        const uint32_t *mask = b.mask[p] + (int64_t)tok0 * rw, *sign = b.sign[p] + (int64_t)tok0 * rw;
+        const int tk = i < Mg ? i : 0;
 #pragma unroll
         for (int r = 0; r < RPW; ++r) {
             const int c = PW * w + 4 * r + g;
-            const bool live = c < P && i < sh.M;
+            const bool live = c < P && i < Mg;
             const int cc = c < P ? c : 0;
             m4[r] = *(const uint4 *)(mask + (int64_t)tk * rw + 4 * cc);
             s4[r] = *(const uint4 *)(sign + (int64_t)tk * rw + 4 * cc);
@@ -180,9 +182,10 @@ __global__ __launch_bounds__(64 * MAXW) void k_gemv_fp4(DecodeBatch b, DecodeSha
     // reduction over the wavefronts and epilogue, TR tiles per round.  Item x of a tile sums the KW
     // partials of token x / 4, channels 4 (x % 4) .. + 3  (accumulator layout: lane l, register v
     // -> channel 4 (l / 16) + v, token l % 16).
-    const ScaleArg sa{b.s_a[p], b.s_a[p] ? sh.a_mode : 0}, sw{b.s_w[p], b.s_w[p] ? sh.w_mode : 0};
-    int32_t *accp = b.acc[p];
-    uint16_t *out = b.out[p];
+    const ScaleArg sa{b.s_a[p] && sh.a_mode == 2 ? b.s_a[p] + tok0 : b.s_a[p], b.s_a[p] ? sh.a_mode : 0};
+    const ScaleArg sw{b.s_w[p], b.s_w[p] ? sh.w_mode : 0};
+    int32_t *accp = b.acc[p] ? b.acc[p] + (int64_t)tok0 * sh.N : nullptr;
+    uint16_t *out = b.out[p] ? b.out[p] + (int64_t)tok0 * sh.ldo : nullptr;
     const bool vec_ok = ((sh.ldo & 3) == 0) && (((uintptr_t)out & 7) == 0);
 #pragma unroll
     for (int t0 = 0; t0 < T; t0 += TR) {
@@ -195,7 +198,7 @@ __global__ __launch_bounds__(64 * MAXW) void k_gemv_fp4(DecodeBatch b, DecodeSha
             v4f s = v4f{0.f, 0.f, 0.f, 0.f};
             for (int ww = 0; ww < KW; ++ww) s += s_red[(tt * KW + ww) * 64 + cg * 16 + token];
             const int64_t n = 16 * (tile0 + t0 + tt) + 4 * cg;
-            if (token >= sh.M || n >= sh.N) continue;
+            if (token >= Mg || n >= sh.N) continue;
             const float fa = load_scale(sa, token);
             uint16_t *dstp = out + (int64_t)token * sh.ldo + n;
             int32_t *accq = accp + (int64_t)token * sh.N + n;
@@ -242,11 +245,11 @@ hipError_t launch_cfg(const DecodeBatch &b, int count, const DecodeShape &sh, hi
     const size_t lds = lds_patch > lds_red ? lds_patch : lds_red;
     if (lds > 64 * 1024) return hipErrorInvalidValue;
     if (KW <= 4)
-        hipLaunchKernelGGL((k_gemv_fp4<RPW, T, PF, 4>), dim3(grid, count), dim3(64 * KW), lds, st, b, sh);
+        hipLaunchKernelGGL((k_gemv_fp4<RPW, T, PF, 4>), dim3(grid, count, (sh.M + 15) / 16), dim3(64 * KW), lds, st, b, sh);
     else if (KW <= 8)
-        hipLaunchKernelGGL((k_gemv_fp4<RPW, T, PF, 8>), dim3(grid, count), dim3(64 * KW), lds, st, b, sh);
+        hipLaunchKernelGGL((k_gemv_fp4<RPW, T, PF, 8>), dim3(grid, count, (sh.M + 15) / 16), dim3(64 * KW), lds, st, b, sh);
     else
-        hipLaunchKernelGGL((k_gemv_fp4<RPW, T, PF, 16>), dim3(grid, count), dim3(64 * KW), lds, st, b, sh);
+        hipLaunchKernelGGL((k_gemv_fp4<RPW, T, PF, 16>), dim3(grid, count, (sh.M + 15) / 16), dim3(64 * KW), lds, st, b, sh);
     return hipGetLastError();
 }
 
@@ -259,7 +262,7 @@ hipError_t launch_shape(const DecodeBatch &b, int count, const DecodeShape &sh, 
     while (RPW < 4 && (chunks + RPW - 1) / RPW > 8) ++RPW;
     if ((chunks + RPW - 1) / RPW > 8 && (chunks + 1) / 2 <= 16) RPW = 2;
     // tiles per workgroup: as many as still leave about 1024 workgroups in the launch
-    const int64_t work = (int64_t)tiles * count;
+    const int64_t work = (int64_t)tiles * count * ((sh.M + 15) / 16);
     int T = work >= 8 * 1024 ? 8 : work >= 4 * 1024 ? 4 : 2;
     if (RPW >= 3 && T > 4) T = 4;
     int PF = T >= 8 ? 4 : 2;
@@ -279,10 +282,11 @@ hipError_t launch_shape(const DecodeBatch &b, int count, const DecodeShape &sh, 
 
 }  // namespace
 
-// 1..16 tokens; K up to 15 wavefronts x 4 chunks x 512 (their LDS patches fill 64 KiB)
+// 1..64 tokens (groups of 16 on grid.z, each streaming the weights: the repeats hit the caches);
+// K up to 15 wavefronts x 4 chunks x 512 (their LDS patches fill 64 KiB)
 bool gemv_fp4_supported(const GemmArgs &g)
 {
-    return g.M >= 1 && g.M <= 16 && g.N >= 1 && g.N <= (1 << 30) && g.rw >= 4 && (g.rw + 15) / 16 <= 60;
+    return g.M >= 1 && g.M <= 64 && g.N >= 1 && g.N <= (1 << 30) && g.rw >= 4 && (g.rw + 15) / 16 <= 60;
 }
 
 hipError_t launch_gemv_fp4_grouped(const GemmArgs *gs, int count, hipStream_t st)

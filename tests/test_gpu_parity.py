@@ -154,7 +154,8 @@ def test_gemm_matches_oracle(M, N, K, path):
 DECODE_SHAPES = [(1, 7, 33), (2, 130, 128), (3, 257, 1000), (1, 1001, 4096), (4, 999, 4096), (8, 300, 4096),
                  (5, 258, 8192), (1, 515, 11008), (4, 130, 11008), (8, 67, 11008), (2, 70, 16384),
                  (3, 40, 16512), (9, 100, 4096), (13, 77, 1408), (16, 257, 11008), (16, 90, 768),
-                 (16, 40, 17000), (7, 33, 30000), (12, 16, 512), (15, 17, 513)]
+                 (16, 40, 17000), (7, 33, 30000), (12, 16, 512), (15, 17, 513), (17, 100, 4096), (33, 70, 11008),
+                 (64, 130, 1000), (48, 17, 128)]
 
 
 @pytest.mark.parametrize("M,N,K", DECODE_SHAPES)
@@ -175,7 +176,7 @@ def test_matrix_core_decode_every_work_split(rpw, tiles, pf):
     _say("decode fp4 split", rpw, tiles, pf)
     B.set_tile(2000 + 1024 * pf + 64 * rpw + tiles)
     try:
-        for M, N, K in [(16, 100, 4096), (11, 70, 11008), (1, 33, 200), (5, 1000, 1000)]:
+        for M, N, K in [(16, 100, 4096), (11, 70, 11008), (1, 33, 200), (5, 1000, 1000), (40, 50, 600)]:
             if -(-B.plane_row_words(K) // 16) > 16 * rpw:
                 continue
             t, w, s_a, s_w = _gemm_case(2500 + M + rpw, M, N, K, p0=0.5)
@@ -312,7 +313,7 @@ def test_prepare_once_feed_several_weight_matrices(path):
 
 
 @pytest.mark.parametrize("path", [B.PATH_AUTO, B.PATH_POPC, B.PATH_FP4])
-@pytest.mark.parametrize("M,N,K,count", [(1, 300, 4096, 3), (4, 130, 11008, 2), (8, 70, 1000, 35), (16, 64, 512, 2)])
+@pytest.mark.parametrize("M,N,K,count", [(1, 300, 4096, 3), (4, 130, 11008, 2), (8, 70, 1000, 35), (16, 64, 512, 2), (37, 50, 640, 3)])
 def test_gemm_grouped_matches_oracle(M, N, K, count, path):
     _say("grouped", M, N, K, count, path)
     t, _, s_a, _ = _gemm_case(3000 + M, M, N, K, p0=0.5)
