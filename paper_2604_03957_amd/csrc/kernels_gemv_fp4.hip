@@ -265,7 +265,7 @@ hipError_t launch_shape(const DecodeBatch &b, int count, const DecodeShape &sh, 
     const int64_t work = (int64_t)tiles * count * ((sh.M + 15) / 16);
     int T = work >= 8 * 1024 ? 8 : work >= 4 * 1024 ? 4 : 2;
     if (RPW >= 3 && T > 4) T = 4;
-    int PF = T >= 8 ? 4 : 2;
+    int PF = T >= 4 ? 4 : 2;
     if (g_force_rpw) {
         if ((chunks + g_force_rpw - 1) / g_force_rpw <= 16) RPW = g_force_rpw;
         if (g_force_t) T = g_force_t;
@@ -274,7 +274,7 @@ hipError_t launch_shape(const DecodeBatch &b, int count, const DecodeShape &sh, 
 #define BWTA_DEC(R_, T_, P_) if (RPW == R_ && T == T_ && PF == P_) return launch_cfg<R_, T_, P_>(b, count, sh, st);
     BWTA_DEC(1, 2, 2) BWTA_DEC(1, 8, 2) BWTA_DEC(1, 8, 4)
     BWTA_DEC(2, 2, 2) BWTA_DEC(2, 4, 2) BWTA_DEC(2, 8, 2) BWTA_DEC(2, 8, 4) BWTA_DEC(2, 16, 4)
-    BWTA_DEC(3, 2, 2) BWTA_DEC(3, 4, 2) BWTA_DEC(3, 8, 2) BWTA_DEC(3, 8, 4)
+    BWTA_DEC(3, 2, 2) BWTA_DEC(3, 4, 2) BWTA_DEC(3, 8, 2) BWTA_DEC(3, 8, 4) BWTA_DEC(3, 4, 4) BWTA_DEC(2, 4, 4) BWTA_DEC(4, 4, 4)
     BWTA_DEC(4, 2, 2) BWTA_DEC(4, 4, 2) BWTA_DEC(4, 8, 2) BWTA_DEC(4, 8, 4)
 #undef BWTA_DEC
     return hipErrorInvalidValue;
