@@ -483,7 +483,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the BWTA hot path is a single-GPU kernel "
-              "path; sharding is described in DESIGN.md). Re-run with --gpus 1.", file=sys.stderr)
+              "path that uses no collectives). Re-run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
     import torch
     if not torch.cuda.is_available():

@@ -220,8 +220,8 @@ int bwta_set_path(int path);
 int bwta_get_path(void);
 /* Which family AUTO resolves to for a shape: BWTA_PATH_POPC, BWTA_PATH_MFMA or BWTA_PATH_FP4. */
 int bwta_auto_path(int M, int N, int K);
-/* Tuning hook for benchmark sweeps: force the FP4 kernel's per-wavefront tile (22, 24, 42, 44 =
- * blocks of 32 rows x 32 columns per wavefront), the popcount decode kernel's row split (1000 +
+/* Tuning hook for benchmark sweeps: force the FP4 kernel's per-wavefront tile (22, 21, 12, 11 =
+ * blocks of 32 rows x 32 columns per wavefront; 23 = 22 at three wavefronts per SIMD), the popcount decode kernel's row split (1000 +
  * 16 * lanes per row + chunks per lane) or the matrix-core decode kernel's work split (2000 +
  * 1024 * ring depth + 64 * chunks per wavefront + tiles per workgroup); 0 restores the built-in
  * choices.  Results do not depend on it. */

@@ -530,16 +530,12 @@ hipError_t launch_gemm_fp4(const GemmArgs &g, uint32_t *frag, bool frag_ready, h
     switch (g_fp4_tile) {  // forced tile (tuning sweeps); 0 = heuristic below
     case 22: return launch<2, 2, 2, 2, 2, false>(g, frag, s_pad, st);
     case 23: return launch<2, 2, 2, 2, 3, false>(g, frag, s_pad, st);
-    case 24: return launch<2, 4, 2, 2, 2, false>(g, frag, s_pad, st);
-    case 42: return launch<4, 2, 2, 2, 2, false>(g, frag, s_pad, st);
     case 21: return launch<2, 1, 2, 2, 3, false>(g, frag, s_pad, st);
     case 12: return launch<1, 2, 2, 2, 3, false>(g, frag, s_pad, st);
     case 11: return launch<1, 1, 2, 2, 4, false>(g, frag, s_pad, st);
     case 2216: return launch<2, 2, 2, 2, 2, false, 1, 16>(g, frag, s_pad, st);
     case 22216: return launch<2, 2, 2, 2, 2, false, 2, 16>(g, frag, s_pad, st);
     case 222: return launch<2, 2, 2, 2, 2, false, 2>(g, frag, s_pad, st);
-    case 322: return launch<2, 2, 2, 2, 3, false, 3>(g, frag, s_pad, st);
-    case 422: return launch<2, 2, 2, 2, 2, false, 4>(g, frag, s_pad, st);
     default: break;
     }
     // measured: long K runs best with 2 wavefronts per SIMD (179 registers), short K with 3
