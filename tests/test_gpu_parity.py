@@ -167,9 +167,9 @@ def test_decode_shaped_gemm_matches_oracle(M, N, K):
     assert _check_gemm(t, w, s_a, s_w, B.PATH_FP4, dirty_sign=True)
 
 
-@pytest.mark.parametrize("rpw,tiles,pf", [(1, 2, 2), (1, 8, 2), (1, 8, 4), (2, 2, 2), (2, 4, 2), (2, 8, 2), (2, 8, 4),
-                                          (2, 16, 4), (3, 2, 2), (3, 4, 2), (3, 8, 2), (3, 8, 4), (4, 2, 2), (4, 4, 2), (2, 4, 4), (3, 4, 4), (4, 4, 4),
-                                          (4, 8, 2), (4, 8, 4)])
+@pytest.mark.parametrize("rpw,tiles,pf", [(1, 2, 2), (1, 8, 2), (1, 8, 4), (1, 6, 3), (2, 2, 2), (2, 4, 2), (2, 8, 2),
+                                          (2, 8, 4), (2, 16, 4), (2, 6, 3), (2, 4, 4), (3, 2, 2), (3, 4, 2), (3, 8, 2),
+                                          (3, 6, 3), (3, 9, 3), (4, 2, 2), (4, 4, 2), (4, 8, 2)])
 def test_matrix_core_decode_every_work_split(rpw, tiles, pf):
     """Chunks per wavefront x channel tiles per workgroup x ring depth of the matrix-core decode
     kernel, on shapes with ragged N, a K tail inside a chunk, and more tiles than one workgroup takes."""
