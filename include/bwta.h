@@ -186,6 +186,9 @@ int bwta_quantize_pack_bool(const void *A, int64_t lda, const void *s_a, int sca
  *   s_a, s_b   fp16 scales; VECTOR means one per row of every batch ([batch, M] / [batch, N]).
  *   acc        optional int32 [batch, M, N] (dense); out optional fp16, row stride ldo >= N,
  *              batches stride_out elements apart.  At least one of acc / out.
+ * Runs on the FP4 matrix cores (+-1 and 0 are exact E2M1 values; fp32 accumulation of integers
+ * below 2^24 is exact); bwta_set_path(BWTA_PATH_POPC) selects the wave64 popcount kernel
+ * instead.  Both give identical bits.
  * Errors as bwta_gemm; nothing is enqueued on error.
  */
 int bwta_matmul_tt(const uint32_t *maskA, const uint32_t *signA, int64_t strideA, const uint32_t *maskB,

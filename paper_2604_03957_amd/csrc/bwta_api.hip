@@ -299,6 +299,7 @@ int bwta_matmul_tt(const uint32_t *maskA, const uint32_t *signA, int64_t strideA
                          {(const uint16_t *)s_a, s_a ? a_scale_mode : BWTA_SCALE_NONE},
                          {(const uint16_t *)s_b, s_b ? b_scale_mode : BWTA_SCALE_NONE},
                          alpha, acc, (uint16_t *)out, ldo, (int64_t)M * N, stride_out};
+    bwta::set_matmul_tt_popc(g_path.load(std::memory_order_relaxed) == BWTA_PATH_POPC);  // comparison path
     return hip_result(bwta::launch_matmul_tt(g, (hipStream_t)stream));
 }
 
@@ -354,9 +355,10 @@ int bwta_auto_path(int M, int N, int K)
 {
     (void)N;
     (void)K;
-    // one or two tokens: the popcount decode kernel; more: the FP4 matrix cores (decode kernel up to
-    // 64 tokens, tiled kernel above)
-    return M > 2 ? BWTA_PATH_FP4 : BWTA_PATH_POPC;
+    // one token: the popcount decode kernel; more: the FP4 matrix cores (decode kernel up to 64
+    // tokens, tiled kernel above).  Measured: at two tokens the popcount kernel is level with the
+    // matrix cores at K = 4096 and a third slower at K = 11008.
+    return M > 1 ? BWTA_PATH_FP4 : BWTA_PATH_POPC;
 }
 
 int bwta_version(void) { return 1; }

@@ -96,27 +96,35 @@ __global__ __launch_bounds__(256) void k_quantize_to_fp4(const uint16_t *__restr
     const int rb = blockIdx.y, m = rb * 32 + row;
     const int q0 = 2 * QF_R * blockIdx.x + (quad >> 5);  // first plane word of this quad; then every second one
 
-    // thresholds: 0.5 s is exact.  An invalid scale turns them into NaN, against which every compare
-    // fails; elements past K are loaded as +0 and fail both compares as well, so the element loop
-    // needs no validity logic: convert, two compares, two selects, one shift-or.
-    float hthr = __builtin_nanf("");
-    if (m < M) {
-        const float s = load_scale(s_a, m);
-        if ((s > 0.0f) && (s < __builtin_inff())) hthr = 0.5f * s;
-    }
-    const float nthr = -hthr;
+    // The scale is requested first and every data load right behind it; nothing is waited for
+    // until all of the thread's requests are out (a wait in front of the data loads would put one
+    // memory round trip in front of the other in every workgroup).
+    const int mc = m < M ? m : 0;
+    const bool have_scale = s_a.mode != 0 && s_a.ptr != nullptr;
+    const uint16_t s_bits = *(have_scale ? s_a.ptr + (s_a.mode == 1 ? 0 : mc) : A);  // no scale: a dropped read
 
-    uint4 x[QF_R];  // all of the thread's loads are issued before the first is used
+    uint4 x[QF_R];
+    if (vec_ok) {  // rows are 16-byte aligned and K is a multiple of 8: whole 128-bit loads only
 #pragma unroll
-    for (int it = 0; it < QF_R; ++it) {
-        const int k0 = 32 * (q0 + 2 * it) + 8 * j;
-        x[it] = make_uint4(0, 0, 0, 0);
-        if (m < M && k0 < K) {
-            const uint16_t *src = A + (int64_t)m * lda + k0;
-            const int nvalid = K - k0 >= 8 ? 8 : K - k0;
-            if (nvalid == 8 && vec_ok) {
-                x[it] = *(const uint4 *)src;
-            } else {
+        for (int it = 0; it < QF_R; ++it) {
+            const int k0 = 32 * (q0 + 2 * it) + 8 * j;
+            const bool inb = m < M && k0 < K;  // lanes outside re-read the first bytes and drop them
+            x[it] = *(const uint4 *)(A + (inb ? (int64_t)m * lda + k0 : 0));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int it = 0; it < QF_R; ++it) {
+            const int k0 = 32 * (q0 + 2 * it) + 8 * j;
+            if (!(m < M && k0 < K)) x[it] = make_uint4(0, 0, 0, 0);
+        }
+    } else {
+#pragma unroll
+        for (int it = 0; it < QF_R; ++it) {
+            const int k0 = 32 * (q0 + 2 * it) + 8 * j;
+            x[it] = make_uint4(0, 0, 0, 0);
+            if (m < M && k0 < K) {
+                const uint16_t *src = A + (int64_t)m * lda + k0;
+                const int nvalid = K - k0 >= 8 ? 8 : K - k0;
                 uint16_t v[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) v[e] = e < nvalid ? src[e] : (uint16_t)0;
@@ -125,6 +133,17 @@ __global__ __launch_bounds__(256) void k_quantize_to_fp4(const uint16_t *__restr
             }
         }
     }
+
+    // thresholds: 0.5 s is exact.  An invalid scale turns them into NaN, against which every compare
+    // fails; elements past K are loaded as +0 and fail both compares as well, so the element loop
+    // needs no validity logic: convert, two compares, two selects, one shift-or.
+    float hthr = __builtin_nanf("");
+    {
+        const float s = have_scale ? half_bits_to_float(s_bits) : 1.0f;
+        if (m < M && (s > 0.0f) && (s < __builtin_inff())) hthr = 0.5f * s;
+    }
+    const float nthr = -hthr;
+
 #pragma unroll
     for (int it = 0; it < QF_R; ++it) {
         const int q = q0 + 2 * it;
@@ -288,9 +307,17 @@ void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, int ti
     // The tile's scales are requested before anything else and parked in LDS with the first weight
     // slab, so the epilogue never waits on a global load.
     float *sc_lds = (float *)(smem + C::WORK_BYTES / 4);  // [BN] channel scales, then [BM] token scales
-    float my_sw = 0.0f, my_sa = 0.0f;
-    if (tid < C::BN && n0 + tid < g.N) my_sw = load_scale(g.s_w, n0 + tid);
-    if (tid < C::BM && m0 + tid < g.M) my_sa = load_scale(g.s_a, m0 + tid);
+    // Every thread issues both loads (one with nothing to fetch re-reads the weights' first bytes and
+    // drops them) and the bits are converted only where they are parked: a conditional load is
+    // waited for inside its branch, which would put two memory round trips in front of the
+    // operand requests of every workgroup.
+    const bool want_sw = tid < C::BN && n0 + tid < g.N, want_sa = tid < C::BM && m0 + tid < g.M;
+    const bool have_sw = want_sw && g.s_w.mode != 0 && g.s_w.ptr != nullptr;
+    const bool have_sa = want_sa && g.s_a.mode != 0 && g.s_a.ptr != nullptr;
+    const uint16_t *scale_safe = (const uint16_t *)g.wsign;
+    const uint16_t sw_bits = *(have_sw ? g.s_w.ptr + (g.s_w.mode == 1 ? 0 : n0 + tid) : scale_safe);
+    const uint16_t sa_bits = *(have_sa ? g.s_a.ptr + (g.s_a.mode == 1 ? 0 : m0 + tid) : scale_safe);
+    __builtin_amdgcn_sched_barrier(0);  // requested first, so parking them waits for nothing younger
 
     uint4 ring[D][WM];
     fetch_w(0, pwbuf[0]);
@@ -298,8 +325,8 @@ void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, int ti
     for (int s = 0; s < D; ++s) load_a(ring[s], 8 * (kg + KS * (s / 8)) + (s & 7));
     stage_w(0, pwbuf[0]);
     if (WPF == 2 && niter > 1) fetch_w(1, pwbuf[WPF - 1]);  // staged at the end of iteration 0
-    if (tid < C::BN) sc_lds[tid] = my_sw;
-    if (tid < C::BM) sc_lds[C::BN + tid] = my_sa;
+    if (tid < C::BN) sc_lds[tid] = have_sw ? half_bits_to_float(sw_bits) : (want_sw ? 1.0f : 0.0f);
+    if (tid < C::BM) sc_lds[C::BN + tid] = have_sa ? half_bits_to_float(sa_bits) : (want_sa ? 1.0f : 0.0f);
     __syncthreads();
 
     int buf = 0;
@@ -499,7 +526,7 @@ hipError_t launch_quantize_to_fp4(const void *A, int64_t lda, ScaleArg s_a, int 
 {
     const int rw = 4 * ((K + 127) / 128);
     const int rb_pad = fp4_rb_pad(M), s_pad = fp4_s_pad(rw);
-    const int vec_ok = (((uintptr_t)A % 16) == 0 && (lda % 8) == 0) ? 1 : 0;
+    const int vec_ok = (((uintptr_t)A % 16) == 0 && (lda % 8) == 0 && (K % 8) == 0) ? 1 : 0;
     const int64_t units = (int64_t)s_pad * rb_pad;  // workgroups at one k step per thread
     if (units >= 4 * 2048)
         hipLaunchKernelGGL(k_quantize_to_fp4<4>, dim3((s_pad + 3) / 4, rb_pad), dim3(256), 0, st, (const uint16_t *)A, lda,

@@ -44,6 +44,8 @@ __device__ __forceinline__ int group_sum(int v)
     return v;
 }
 
+typedef unsigned v4u_t __attribute__((ext_vector_type(4)));
+
 struct GemvBatch {
     static constexpr int MAX = 64;
     const uint32_t *mask[MAX], *sign[MAX], *wsign[MAX];
@@ -57,7 +59,7 @@ struct GemvShape {
     int64_t ldo;
 };
 
-template <int MT, int G, int NCH, int UNR>
+template <int MT, int G, int NCH, int UNR, bool NT>
 __global__ __launch_bounds__(256) void k_gemv_popc(GemvBatch b, GemvShape sh)
 {
     const int lane = threadIdx.x & 63;
@@ -77,9 +79,42 @@ __global__ __launch_bounds__(256) void k_gemv_popc(GemvBatch b, GemvShape sh)
         coff[j] = 4 * (c < sh.C4 ? c : sh.C4 - 1);
     }
 
-    // weight rows of this wavefront: UNR passes, issued first (HBM latency); rows past N are
-    // clamped to the last row and never stored
+    // Request order: the scales the epilogue needs, the activation rows (small, cache-resident), then
+    // the weight rows of all UNR passes.  Memory returns in request order, so the activations can be
+    // parked in LDS while the weights are still in flight, each pass waits for its own rows only,
+    // and the end of the kernel waits for no load at all.  Every lane issues every load (a lane with
+    // nothing to fetch reads the matrix's first bytes and drops them), so no wait hides in a branch.
+    const ScaleArg sa{b.s_a[p], b.s_a[p] ? sh.a_mode : 0}, sw{b.s_w[p], b.s_w[p] ? sh.w_mode : 0};
+    const bool writer = cl < sh.M;  // lane cl of a group writes token cl (G >= 8 >= MT)
+    const uint16_t *safe = (const uint16_t *)wsign;
     const int64_t row0 = ((int64_t)gw * UNR) * RPP + sub;
+    const uint16_t sa_raw = *((sa.mode && writer) ? sa.ptr + (sa.mode == 1 ? 0 : cl) : safe);
+    uint16_t sw_raw[UNR];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+        int64_t n = row0 + (int64_t)u * RPP;
+        n = n < sh.N ? n : sh.N - 1;
+        sw_raw[u] = *(sw.mode ? sw.ptr + (sw.mode == 1 ? 0 : n) : safe);
+    }
+
+    // activation rows: staged once per workgroup in LDS (coalesced), then each lane keeps the
+    // chunks it needs in registers.  Layout: [token][plane][chunk] of 16 bytes.
+    extern __shared__ __attribute__((aligned(16))) uint4 s_act[];
+    constexpr int NSTAGE = (MT * 2 * G * NCH + 255) / 256;  // staging loads per thread
+    constexpr bool EARLY = NSTAGE <= 2;  // more rows than that are staged by a loop behind the weights
+    constexpr int NST = EARLY ? NSTAGE : 0;
+    const int act_pieces = sh.M * 2 * sh.C4;
+    uint4 stage[NST > 0 ? NST : 1];
+#pragma unroll
+    for (int k = 0; k < NST; ++k) {
+        const int idx = threadIdx.x + 256 * k;
+        const int ic = idx < act_pieces ? idx : 0;
+        const int c = ic % sh.C4, pl = (ic / sh.C4) & 1, m = ic / (2 * sh.C4);
+        stage[k] = *(const uint4 *)((pl ? sign : mask) + (int64_t)m * rw + 4 * c);
+    }
+
+    // weight rows of this wavefront: UNR passes; rows past N are clamped to the last row and never
+    // stored.  Rows that are whole 128-byte lines are streamed past the caches (NT).
     uint4 w[UNR][NCH];
 #pragma unroll
     for (int u = 0; u < UNR; ++u) {
@@ -87,15 +122,24 @@ __global__ __launch_bounds__(256) void k_gemv_popc(GemvBatch b, GemvShape sh)
         n = n < sh.N ? n : sh.N - 1;
         const uint32_t *wrow = wsign + n * rw;
 #pragma unroll
-        for (int j = 0; j < NCH; ++j) w[u][j] = *(const uint4 *)(wrow + coff[j]);
+        for (int j = 0; j < NCH; ++j) {
+            const v4u_t *src = (const v4u_t *)(wrow + coff[j]);
+            const v4u_t x = NT ? __builtin_nontemporal_load(src) : *src;
+            w[u][j] = make_uint4(x[0], x[1], x[2], x[3]);
+        }
     }
+    __builtin_amdgcn_sched_barrier(0);  // nothing above is waited for before every request is out
 
-    // activation rows: staged once per workgroup in LDS (coalesced), then each lane keeps the
-    // chunks it needs in registers.  Layout: [token][plane][chunk] of 16 bytes.
-    extern __shared__ __attribute__((aligned(16))) uint4 s_act[];
-    for (int idx = threadIdx.x; idx < sh.M * 2 * sh.C4; idx += 256) {
-        const int c = idx % sh.C4, pl = (idx / sh.C4) & 1, m = idx / (2 * sh.C4);
-        s_act[idx] = *(const uint4 *)((pl ? sign : mask) + (int64_t)m * rw + 4 * c);
+#pragma unroll
+    for (int k = 0; k < NST; ++k) {
+        const int idx = threadIdx.x + 256 * k;
+        if (idx < act_pieces) s_act[idx] = stage[k];
+    }
+    if (!EARLY) {
+        for (int idx = threadIdx.x; idx < act_pieces; idx += 256) {
+            const int c = idx % sh.C4, pl = (idx / sh.C4) & 1, m = idx / (2 * sh.C4);
+            s_act[idx] = *(const uint4 *)((pl ? sign : mask) + (int64_t)m * rw + 4 * c);
+        }
     }
     __syncthreads();
     const uint4 zero4 = make_uint4(0, 0, 0, 0);
@@ -115,11 +159,9 @@ __global__ __launch_bounds__(256) void k_gemv_popc(GemvBatch b, GemvShape sh)
         my_nnz = (cl == m) ? c : my_nnz;
     }
 
-    const ScaleArg sa{b.s_a[p], b.s_a[p] ? sh.a_mode : 0}, sw{b.s_w[p], b.s_w[p] ? sh.w_mode : 0};
     int32_t *acc = b.acc[p];
     uint16_t *out = b.out[p];
-    const bool writer = cl < sh.M;  // lane cl of a group writes token cl (G >= 8 >= MT)
-    const float my_sa = writer ? load_scale(sa, cl) : 0.0f;
+    const float my_sa = (sa.mode && writer) ? half_bits_to_float(sa_raw) : 1.0f;
 #pragma unroll
     for (int u = 0; u < UNR; ++u) {
         const int64_t n = row0 + (int64_t)u * RPP;
@@ -135,7 +177,8 @@ __global__ __launch_bounds__(256) void k_gemv_popc(GemvBatch b, GemvShape sh)
         if (writer && n < sh.N) {
             const int a = my_nnz - 2 * my_cnt;
             if (acc) acc[(int64_t)cl * sh.N + n] = a;
-            if (out) out[(int64_t)cl * sh.ldo + n] = scaled_to_half(a, my_sa * load_scale(sw, (int)n));
+            const float my_sw = sw.mode ? half_bits_to_float(sw_raw[u]) : 1.0f;
+            if (out) out[(int64_t)cl * sh.ldo + n] = scaled_to_half(a, my_sa * my_sw);
         }
     }
 }
@@ -151,7 +194,10 @@ hipError_t launch_t(const GemvBatch &b, int count, const GemvShape &sh, hipStrea
     const int64_t waves = (passes + UNR - 1) / UNR;
     const unsigned grid = (unsigned)((waves + 3) / 4);
     const size_t lds = (size_t)sh.M * 2 * sh.C4 * 16;  // <= 8 * 2 * 128 * 16 = 32 KiB
-    hipLaunchKernelGGL((k_gemv_popc<MT, G, NCH, UNR>), dim3(grid, count), dim3(256), lds, st, b, sh);
+    if ((sh.rw & 31) == 0)
+        hipLaunchKernelGGL((k_gemv_popc<MT, G, NCH, UNR, true>), dim3(grid, count), dim3(256), lds, st, b, sh);
+    else
+        hipLaunchKernelGGL((k_gemv_popc<MT, G, NCH, UNR, false>), dim3(grid, count), dim3(256), lds, st, b, sh);
     return hipGetLastError();
 }
 

@@ -5,8 +5,14 @@
 // Both are  acc = popc(u) - 2 popc(u & (sA ^ sB))  with u = maskA & maskB: a product is non-zero
 // where both operands are, and negative where their signs differ.  A boolean operand is a ternary
 // one whose sign plane is absent (all zero), which turns the expression into the paper's
-// popc(Att & V+) - popc(Att & V-).  Vector ALU, LDS-tiled, wave64: per 32 multiply-accumulates one
-// AND, one three-input boolean op and two popcount-accumulates.
+// popc(Att & V+) - popc(Att & V-).
+//
+// Two kernels compute it.  k_matmul_tt_fp4 (the default) runs the product on the FP4 matrix cores:
+// +1, -1 and 0 are exact E2M1 values and every partial sum is an integer below 2^24, so the fp32
+// accumulators of v_mfma_f32_32x32x64_f8f6f4 hold the popcount result exactly.  Both operands stay
+// bit planes in HBM and LDS and are expanded to nibbles in registers.  k_matmul_tt is the vector-ALU
+// form (LDS-tiled, wave64: per 32 multiply-accumulates one AND, one three-input boolean op and two
+// popcount-accumulates), kept as the comparison path.
 #include "bwta_internal.h"
 
 namespace bwta {
@@ -124,14 +130,246 @@ __global__ __launch_bounds__(256) void k_matmul_tt(MatmulTTArgs g)
     }
 }
 
+
+// ---- matrix-core form -------------------------------------------------------------------------
+// Workgroup = 4 wavefronts (2 x 2) on a 128 x 128 output tile, a wavefront owns 2 x 2 blocks of
+// 32 x 32.  K advances in slabs of 256 (8 plane words per row); a slab of the four planes sits in
+// LDS (double-buffered, one barrier per slab).  Lane (r32, h) of an operand block holds row r32
+// and, for step s of the slab, plane word 4 h + s: a dot product is unchanged by a permutation of
+// k applied to both operands, so a lane may take four consecutive words (one 16-byte LDS read per
+// plane) and deal bit 4 n + d of a word to nibble n of dword d.  The B rows are the instruction's
+// first operand, so a lane ends with four consecutive n of one m and the tile leaves as 16-byte
+// row-contiguous stores.
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+
+constexpr int FT = 128;                 // tile edge
+constexpr int FSW = 8;                  // plane words per slab
+constexpr int FPITCH = 12;              // dwords per LDS row: 16-byte reads at stride 48 B are conflict-free
+constexpr int FPLANE = FT * FPITCH;     // dwords per plane tile
+constexpr int FSTAGE = 4 * FPLANE;      // Am, As, Bm, Bs
+constexpr int FSTRIP_PITCH = 64 + 8;    // halfs per row of a wavefront's output strip
+constexpr int FSMEM_BYTES = 2 * FSTAGE * 4 + 2 * FT * 4;  // two stages, then [128] s_b and [128] s_a as floats
+
+// plane words -> E2M1 nibbles (+1 = 0b0010, -1 = 0b1010, 0 = 0b0000): bit 4 n + d -> nibble n of dword d
+template <bool SIGNED>
+__device__ __forceinline__ v8i widen_t(uint32_t m, uint32_t s, uint32_t m88, uint32_t c22)
+{
+    v8i r;
+    if (SIGNED) {
+        const uint32_t ss = s & m;
+        r[0] = (int)(((ss << 3) & m88) | ((m << 1) & c22));
+        r[1] = (int)(((ss << 2) & m88) | (m & c22));
+        r[2] = (int)(((ss << 1) & m88) | ((m >> 1) & c22));
+        r[3] = (int)((ss & m88) | ((m >> 2) & c22));
+    } else {
+        r[0] = (int)((m << 1) & c22);
+        r[1] = (int)(m & c22);
+        r[2] = (int)((m >> 1) & c22);
+        r[3] = (int)((m >> 2) & c22);
+    }
+    r[4] = r[5] = r[6] = r[7] = 0;
+    return r;
+}
+
+template <bool SIGN_A, bool SIGN_B>
+__global__ __launch_bounds__(256, 2) void k_matmul_tt_fp4(MatmulTTArgs g)
+{
+    extern __shared__ __attribute__((aligned(16))) uint32_t fsm[];
+    float *sc_lds = (float *)(fsm + 2 * FSTAGE);  // [FT] s_b, then [FT] s_a
+    const int tid = threadIdx.x, lane = tid & 63, wl = tid >> 6;
+    const int wm = wl >> 1, wn = wl & 1, r32 = lane & 31, h = lane >> 5;
+    const int m0 = blockIdx.y * FT, n0 = blockIdx.x * FT, b = blockIdx.z;
+    const int rw = g.rw;
+    const uint32_t *planes[4] = {g.maskA + (int64_t)b * g.strideA, SIGN_A ? g.signA + (int64_t)b * g.strideA : nullptr,
+                                 g.maskB + (int64_t)b * g.strideB, SIGN_B ? g.signB + (int64_t)b * g.strideB : nullptr};
+
+    // scales: requested first by every thread (without a scale: a dropped read), parked in LDS with
+    // the first slab, so neither the operand requests nor the epilogue wait for them
+    const ScaleArg sa{g.s_a.ptr && g.s_a.mode == 2 ? g.s_a.ptr + (int64_t)b * g.M : g.s_a.ptr, g.s_a.ptr ? g.s_a.mode : 0};
+    const ScaleArg sb{g.s_b.ptr && g.s_b.mode == 2 ? g.s_b.ptr + (int64_t)b * g.N : g.s_b.ptr, g.s_b.ptr ? g.s_b.mode : 0};
+    const int sidx = tid & (FT - 1);
+    const bool is_b = tid < FT;
+    const ScaleArg &mine = is_b ? sb : sa;
+    const bool want = is_b ? n0 + sidx < g.N : m0 + sidx < g.M;
+    const bool have = want && mine.mode != 0;
+    const uint16_t sc_bits = *(have ? mine.ptr + (mine.mode == 1 ? 0 : (is_b ? n0 : m0) + sidx) : (const uint16_t *)g.maskA);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // slab loader: plane pl, 128 rows x 2 pieces of 16 bytes; thread t takes piece t of every plane
+    const int lrow = tid >> 1, lcol = tid & 1;
+    auto fetch = [&](int slab, uint4(&dst)[4]) {
+        const int kw = slab * FSW + 4 * lcol;
+#pragma unroll
+        for (int pl = 0; pl < 4; ++pl) {
+            dst[pl] = make_uint4(0, 0, 0, 0);
+            if ((pl == 1 && !SIGN_A) || (pl == 3 && !SIGN_B)) continue;
+            const int row = (pl < 2 ? m0 : n0) + lrow, rows = pl < 2 ? g.M : g.N;
+            // rows and words outside the operand re-read its first bytes and are zeroed when staged
+            const bool inside = row < rows && kw < rw;
+            dst[pl] = *(const uint4 *)(planes[pl] + (inside ? (int64_t)row * rw + kw : 0));
+        }
+    };
+    auto stage = [&](int buf, int slab, const uint4(&src)[4]) {
+        const int kw = slab * FSW + 4 * lcol;
+#pragma unroll
+        for (int pl = 0; pl < 4; ++pl) {
+            if ((pl == 1 && !SIGN_A) || (pl == 3 && !SIGN_B)) continue;
+            const int row = (pl < 2 ? m0 : n0) + lrow, rows = pl < 2 ? g.M : g.N;
+            const bool inside = row < rows && kw < rw;
+            *(uint4 *)(fsm + buf * FSTAGE + pl * FPLANE + lrow * FPITCH + 4 * lcol) = inside ? src[pl] : make_uint4(0, 0, 0, 0);
+        }
+    };
+
+    uint32_t m88 = 0x88888888u, c22 = 0x22222222u;  // opaque, so each expansion is one v_and_or_b32
+    asm volatile("" : "+s"(m88));
+    asm volatile("" : "+v"(c22));
+
+    v16f acc[2][2];  // [n block][m block]
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[j][i][v] = 0.0f;
+
+    const int nslab = (rw + FSW - 1) / FSW;
+    auto compute = [&](int buf) {
+        const uint32_t *st = fsm + buf * FSTAGE;
+        v4u am[2], as[2], bm[2], bs[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int ra = (wm * 64 + 32 * i + r32) * FPITCH + 4 * h, rb = (wn * 64 + 32 * i + r32) * FPITCH + 4 * h;
+            am[i] = *(const v4u *)(st + ra);
+            if (SIGN_A) as[i] = *(const v4u *)(st + FPLANE + ra);
+            bm[i] = *(const v4u *)(st + 2 * FPLANE + rb);
+            if (SIGN_B) bs[i] = *(const v4u *)(st + 3 * FPLANE + rb);
+        }
+        // a last slab with fewer than 8 words still takes all four steps: its missing words are zero
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            v8i fa[2], fb[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                fa[i] = widen_t<SIGN_A>(am[i][s], SIGN_A ? as[i][s] : 0u, m88, c22);
+                fb[i] = widen_t<SIGN_B>(bm[i][s], SIGN_B ? bs[i][s] : 0u, m88, c22);
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+                    acc[j][i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[j], fa[i], acc[j][i], 4, 4, 0, 0, 0, 0);
+        }
+    };
+    // One slab is requested ahead (registers) while the current one is multiplied out of LDS; one
+    // barrier per slab.  The last iteration re-requests its own slab, so every iteration issues
+    // the same loads.  (Requesting two slabs ahead was measured: no faster on Att V, slower on Q K^T.)
+    uint4 pre[4];
+    fetch(0, pre);
+    __builtin_amdgcn_sched_barrier(0);
+    stage(0, 0, pre);
+    sc_lds[tid] = have ? half_bits_to_float(sc_bits) : (want ? 1.0f : 0.0f);
+    __syncthreads();
+    int buf = 0;
+    for (int it = 0; it < nslab; ++it) {
+        const int nxt = it + 1 < nslab ? it + 1 : nslab - 1;
+        fetch(nxt, pre);
+        compute(buf);
+        stage(buf ^ 1, nxt, pre);
+        __syncthreads();
+        buf ^= 1;
+    }
+
+    // ---- epilogue.  Lane (r32, h) of block (j, i) holds m = 32 i + r32 and n = 32 j + 8 q + 4 h + e
+    // (register v = 4 q + e).
+    const int m_wave = m0 + wm * 64, n_wave = n0 + wn * 64;
+    if (g.acc) {
+        int32_t *accp = g.acc + (int64_t)b * g.stride_acc;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int m = m_wave + 32 * i + r32;
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int n = n_wave + 32 * j + 8 * (v >> 2) + 4 * h + (v & 3);
+                    if (m < g.M && n < g.N) accp[(int64_t)m * g.N + n] = (int)acc[j][i][v];
+                }
+        }
+    }
+    if (!g.out) return;
+    uint16_t *out = g.out + (int64_t)b * g.stride_out;
+    // out = fp16( acc * s ),  s = fp32( alpha * (s_a * s_b) ): s_a * s_b is exact in fp32, the
+    // multiplication by alpha rounds once, and acc * s is rounded once more, to fp16.
+    // The loop's last barrier retired every read of the slabs, whose LDS the strips reuse.
+    uint16_t *strip = (uint16_t *)fsm + wl * (32 * FSTRIP_PITCH);
+    const float *sb_lds = sc_lds, *sa_lds = sc_lds + FT;
+    const bool full = (m_wave + 64 <= g.M) && (n_wave + 64 <= g.N) && ((g.ldo & 7) == 0) &&
+                      (g.batch == 1 || (g.stride_out & 7) == 0) && (((uintptr_t)g.out & 15) == 0);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const float fa = sa_lds[wm * 64 + 32 * i + r32];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int nl = 32 * j + 8 * q + 4 * h;
+                const float4 fb = *(const float4 *)(sb_lds + wn * 64 + nl);
+                uint2 hv;
+                hv.x = scaled_to_half2(acc[j][i][4 * q], g.alpha * (fa * fb.x), acc[j][i][4 * q + 1], g.alpha * (fa * fb.y));
+                hv.y = scaled_to_half2(acc[j][i][4 * q + 2], g.alpha * (fa * fb.z), acc[j][i][4 * q + 3], g.alpha * (fa * fb.w));
+                *(uint2 *)(strip + r32 * FSTRIP_PITCH + nl) = hv;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+        for (int rr = 0; rr < 32; rr += 8) {
+            const int row = rr + (lane >> 3), c8 = 8 * (lane & 7);
+            const int mo = m_wave + 32 * i + row, n = n_wave + c8;
+            const uint4 qd = *(const uint4 *)(strip + row * FSTRIP_PITCH + c8);
+            uint16_t *dst = out + (int64_t)mo * g.ldo + n;
+            if (full) {
+                const v4u qv = {qd.x, qd.y, qd.z, qd.w};
+                __builtin_nontemporal_store(qv, (v4u *)dst);  // streamed once, never re-read here
+            } else if (mo < g.M && n < g.N) {
+                const uint32_t w[4] = {qd.x, qd.y, qd.z, qd.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (n + e < g.N) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    }
+}
+
+template <bool SIGN_A, bool SIGN_B>
+hipError_t launch_fp4_t(const MatmulTTArgs &g, hipStream_t st)
+{
+    dim3 grid((g.N + FT - 1) / FT, (g.M + FT - 1) / FT, g.batch);
+    hipLaunchKernelGGL((k_matmul_tt_fp4<SIGN_A, SIGN_B>), grid, dim3(256), FSMEM_BYTES, st, g);
+    return hipGetLastError();
+}
+
+int g_matmul_tt_popc = 0;  // comparison path selector
 }  // namespace
 
 hipError_t launch_matmul_tt(const MatmulTTArgs &g, hipStream_t st)
 {
     if (g.M == 0 || g.N == 0 || g.batch == 0) return hipSuccess;
+    if (!g_matmul_tt_popc) {
+        if (g.signA && g.signB) return launch_fp4_t<true, true>(g, st);
+        if (g.signA) return launch_fp4_t<true, false>(g, st);
+        if (g.signB) return launch_fp4_t<false, true>(g, st);
+        return launch_fp4_t<false, false>(g, st);
+    }
     dim3 grid((g.N + BN - 1) / BN, (g.M + BM - 1) / BM, g.batch);
     hipLaunchKernelGGL(k_matmul_tt, grid, dim3(256), 0, st, g);
     return hipGetLastError();
 }
+
+void set_matmul_tt_popc(int on) { g_matmul_tt_popc = on; }
 
 }  // namespace bwta

@@ -9,6 +9,8 @@ namespace bwta {
 namespace {
 
 constexpr int kThreads = 256;
+// four groups per thread only when that still leaves a few workgroups per compute unit
+constexpr int64_t kQuadGroupMinThreads = 1024 * kThreads;
 
 // OR a per-lane byte into its quad's 32-bit word (lane q of the quad supplies byte q).
 __device__ __forceinline__ uint32_t quad_word(uint32_t byte, int lane)
@@ -60,6 +62,10 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack(const void *__restri
     const int nvalid = K - k0 >= 8 ? 8 : (K - k0 > 0 ? K - k0 : 0);
     TernaryBits tb{0u, 0u};
     if (DTYPE == 0 || DTYPE == 2) {
+        // the scale is requested before the data and by every lane (without a scale: a dropped read
+        // of the first element), so the two requests share one memory round trip
+        const bool have_scale = s_a.mode != 0 && s_a.ptr != nullptr;
+        const uint16_t s_bits = *(have_scale ? s_a.ptr + (s_a.mode == 1 ? 0 : m) : (const uint16_t *)A);
         const uint16_t *row = (const uint16_t *)A + (int64_t)m * lda;
         uint16_t v[8];
         if (nvalid == 8 && vec_ok) {
@@ -70,8 +76,8 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack(const void *__restri
 #pragma unroll
             for (int i = 0; i < 8; ++i) v[i] = i < nvalid ? row[k0 + i] : (uint16_t)0;
         }
-        float s = load_scale(s_a, m);
-        bool ok = (s > 0.0f) && (s < __builtin_inff());
+        const float s = have_scale ? half_bits_to_float(s_bits) : 1.0f;
+        const bool ok = (s > 0.0f) && (s < __builtin_inff());
         tb = ternary_bits_fp16(v, nvalid, 0.5f * s, ok);
         if (DTYPE == 2) tb.nz &= ~tb.neg;  // boolean: only a >= 0.5 s counts, and there is no sign plane
     } else {
@@ -100,6 +106,52 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack(const void *__restri
     const int64_t widx = (int64_t)m * rw + (c >> 2);
     if ((lane & 3) == 0) mask[widx] = wm;
     if (DTYPE != 2 && (lane & 3) == 1) sign[widx] = ws;
+}
+
+// The same operation for 16-byte aligned fp16 rows whose K is a multiple of 8 (every group of 8 is
+// whole or entirely padding): a thread takes four groups of one row, a quarter row apart, and
+// issues its scale request and all four 128-bit loads before anything is used, so four times the
+// bytes are in flight per wavefront.  Index space: row m, word w0 in the first quarter of the row,
+// quad lane q; group u is byte-group 4 (w0 + u rw / 4) + q.
+template <int DTYPE>  // 0 = ternary, 2 = boolean
+__global__ __launch_bounds__(kThreads) void k_quantize_pack_vec(const uint16_t *__restrict__ A, int64_t lda,
+                                                                ScaleArg s_a, int M, int K, int rw,
+                                                                uint32_t *__restrict__ mask,
+                                                                uint32_t *__restrict__ sign)
+{
+    const int64_t total = (int64_t)M * rw;  // threads with work: M rows x rw / 4 words x 4 lanes
+    const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const bool live = gid < total;  // whole quads together (rw % 4 == 0)
+    const int64_t gc = live ? gid : 0;
+    const int m = (int)(gc / rw), rem = (int)(gc - (int64_t)m * rw);
+    const int w0 = rem >> 2, q = rem & 3, qw = rw >> 2;
+    const bool have_scale = s_a.mode != 0 && s_a.ptr != nullptr;
+    const uint16_t s_bits = *(have_scale ? s_a.ptr + (s_a.mode == 1 ? 0 : m) : A);
+    const uint16_t *row = A + (int64_t)m * lda;
+    uint4 x[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int k0 = 8 * (4 * (w0 + u * qw) + q);
+        x[u] = *(const uint4 *)(k0 < K ? row + k0 : A);  // padding groups re-read the first bytes and drop them
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    const float s = have_scale ? half_bits_to_float(s_bits) : 1.0f;
+    const bool ok = (s > 0.0f) && (s < __builtin_inff());
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int w = w0 + u * qw, k0 = 8 * (4 * w + q);
+        const uint4 xv = k0 < K ? x[u] : make_uint4(0, 0, 0, 0);
+        const uint16_t v[8] = {(uint16_t)xv.x, (uint16_t)(xv.x >> 16), (uint16_t)xv.y, (uint16_t)(xv.y >> 16),
+                               (uint16_t)xv.z, (uint16_t)(xv.z >> 16), (uint16_t)xv.w, (uint16_t)(xv.w >> 16)};
+        TernaryBits tb = ternary_bits_fp16(v, 8, 0.5f * s, ok);
+        if (DTYPE == 2) tb.nz &= ~tb.neg;
+        const uint32_t wm = quad_word(tb.nz, lane);
+        const uint32_t ws = DTYPE == 2 ? 0u : quad_word(tb.neg, lane);
+        const int64_t widx = (int64_t)m * rw + w;
+        if (live && q == 0) mask[widx] = wm;
+        if (DTYPE != 2 && live && q == 1) sign[widx] = ws;
+    }
 }
 
 template <int DTYPE>
@@ -354,7 +406,10 @@ hipError_t launch_quantize_pack(const void *A, int dtype, int64_t lda, ScaleArg 
     const unsigned grid = (unsigned)((total + kThreads - 1) / kThreads);
     const int elt = dtype == 0 ? 2 : 1;
     const int vec_ok = (((uintptr_t)A % (8 * elt)) == 0 && (lda % 8) == 0) ? 1 : 0;
-    if (dtype == 0)
+    if (dtype == 0 && vec_ok && (K % 8) == 0 && (int64_t)M * rw >= kQuadGroupMinThreads)
+        hipLaunchKernelGGL(k_quantize_pack_vec<0>, dim3((unsigned)(((int64_t)M * rw + kThreads - 1) / kThreads)),
+                           dim3(kThreads), 0, st, (const uint16_t *)A, lda, s_a, M, K, rw, mask, sign);
+    else if (dtype == 0)
         hipLaunchKernelGGL(k_quantize_pack<0>, dim3(grid), dim3(kThreads), 0, st, A, lda, s_a, M, K, rw,
                            mask, sign, vec_ok);
     else
@@ -374,8 +429,12 @@ hipError_t launch_quantize_pack_bool(const void *A, int64_t lda, ScaleArg s_a, i
     if (total == 0) return hipSuccess;
     const unsigned grid = (unsigned)((total + kThreads - 1) / kThreads);
     const int vec_ok = (((uintptr_t)A % 16) == 0 && (lda % 8) == 0) ? 1 : 0;
-    hipLaunchKernelGGL(k_quantize_pack<2>, dim3(grid), dim3(kThreads), 0, st, A, lda, s_a, M, K, rw, mask,
-                       (uint32_t *)nullptr, vec_ok);
+    if (vec_ok && (K % 8) == 0 && (int64_t)M * rw >= kQuadGroupMinThreads)
+        hipLaunchKernelGGL(k_quantize_pack_vec<2>, dim3((unsigned)(((int64_t)M * rw + kThreads - 1) / kThreads)),
+                           dim3(kThreads), 0, st, (const uint16_t *)A, lda, s_a, M, K, rw, mask, (uint32_t *)nullptr);
+    else
+        hipLaunchKernelGGL(k_quantize_pack<2>, dim3(grid), dim3(kThreads), 0, st, A, lda, s_a, M, K, rw, mask,
+                           (uint32_t *)nullptr, vec_ok);
     return hipGetLastError();
 }
 

@@ -42,6 +42,20 @@ def test_bool_pack_matches_oracle(M, K, lda):
     assert np.array_equal(gpu_pack_bool(x, s, lda=lda, K=K), want)
 
 
+@pytest.mark.parametrize("M,K,lda", [(2100, 4096, None), (2300, 3720, 3728)])
+def test_bool_pack_large_aligned_rows(M, K, lda):
+    """Sizes at which the boolean packer takes its four-groups-per-thread kernel."""
+    _say("bool pack large", M, K, lda)
+    x = np.abs(synth.gaussian(60 + M, 1, M * (lda or K))).astype(np.float16).reshape(M, -1)
+    s = synth.scales(60 + M, 2, M)
+    s[3], s[M - 2] = np.nan, -1.0
+    want, _, _ = oracle.pack_act(oracle.boolize(np.ascontiguousarray(x[:, :K]), s))
+    assert np.array_equal(gpu_pack_bool(x, s, lda=lda, K=K), want)
+    one = np.array([0.3], np.float16)
+    want, _, _ = oracle.pack_act(oracle.boolize(np.ascontiguousarray(x[:, :K]), one))
+    assert np.array_equal(gpu_pack_bool(x, one, lda=lda, K=K), want)
+
+
 def test_bool_pack_every_half_pattern_and_bad_scales():
     bits = np.arange(65536, dtype=np.uint32).astype(np.uint16).reshape(64, 1024)
     A = bits.view(np.float16)
@@ -49,6 +63,15 @@ def test_bool_pack_every_half_pattern_and_bad_scales():
         sc = np.array([s], np.float16)
         want, _, _ = oracle.pack_act(oracle.boolize(A, sc))
         assert np.array_equal(gpu_pack_bool(A, sc), want), s
+
+
+@pytest.fixture(params=["matrix_cores", "popcount"])
+def family(request):
+    """Both kernels behind bwta_matmul_tt: the FP4 matrix-core one (default) and the wave64 popcount one."""
+    if request.param == "popcount":
+        B.set_path(B.PATH_POPC)
+    yield request.param
+    B.set_path(B.PATH_AUTO)
 
 
 def _operands(seed, batch, M, N, K, a_bool, p0a=0.45, p0b=0.5):
@@ -59,7 +82,7 @@ def _operands(seed, batch, M, N, K, a_bool, p0a=0.45, p0b=0.5):
     return a, b
 
 
-def _run(a, b, s_a, s_b, alpha, a_bool, *, pad_a=0, pad_b=0, ldo=None, pad_out=0, dirty=False):
+def _run(a, b, s_a, s_b, alpha, a_bool, *, pad_a=0, pad_b=0, ldo=None, pad_out=0, dirty=False, b_bool=False):
     batch, M, K = a.shape
     N = b.shape[1]
     rw = B.plane_row_words(K)
@@ -78,7 +101,7 @@ def _run(a, b, s_a, s_b, alpha, a_bool, *, pad_a=0, pad_b=0, ldo=None, pad_out=0
     stride_out = M * ldo + pad_out
     acc = torch.full((batch, M, N), 12345, dtype=torch.int32, device=DEV)
     out = torch.full((batch * stride_out,), float("nan"), dtype=torch.float16, device=DEV)
-    B.bwta_matmul_tt(dev(ma), None if a_bool else dev(sa), dev(mb), dev(sb), dev(s_a), dev(s_b), acc, out,
+    B.bwta_matmul_tt(dev(ma), None if a_bool else dev(sa), dev(mb), None if b_bool else dev(sb), dev(s_a), dev(s_b), acc, out,
                      batch=batch, M=M, N=N, K=K, alpha=alpha, strideA=M * rw + pad_a, strideB=N * rw + pad_b,
                      ldo=ldo, stride_out=stride_out)
     torch.cuda.synchronize()
@@ -99,11 +122,11 @@ def _run(a, b, s_a, s_b, alpha, a_bool, *, pad_a=0, pad_b=0, ldo=None, pad_out=0
     return exact
 
 
-QK_SHAPES = [(1, 64, 64, 128), (3, 70, 130, 128), (2, 1, 5, 33), (2, 257, 65, 64), (1, 130, 200, 1000)]
+QK_SHAPES = [(1, 64, 64, 128), (3, 70, 130, 128), (2, 1, 5, 33), (2, 257, 65, 64), (1, 130, 200, 1000), (1, 129, 260, 1300)]
 
 
 @pytest.mark.parametrize("batch,M,N,K", QK_SHAPES)
-def test_qk_product_matches_oracle(batch, M, N, K):
+def test_qk_product_matches_oracle(batch, M, N, K, family):
     """BWTA_QK: ternary(Q) x ternary(K)^T with layerwise scales and 1/sqrt(D)."""
     _say("qk", batch, M, N, K)
     q, k = _operands(600 + M, batch, M, N, K, a_bool=False)
@@ -112,14 +135,21 @@ def test_qk_product_matches_oracle(batch, M, N, K):
 
 
 @pytest.mark.parametrize("batch,M,N,K", [(1, 64, 64, 64), (3, 70, 64, 200), (2, 1, 5, 33), (2, 200, 128, 1000)])
-def test_att_v_product_matches_oracle(batch, M, N, K):
+def test_att_v_product_matches_oracle(batch, M, N, K, family):
     """BWTA_Att: bool(Att) x ternary(V); V arrives transposed (packed along the sequence)."""
     _say("att", batch, M, N, K)
     att, vt = _operands(700 + M, batch, M, N, K, a_bool=True, p0a=0.8)
     assert _run(att, vt, synth.scales(700, 1, 1), synth.scales(700, 2, 1), 1.0, True, dirty=True)
 
 
-def test_vector_scales_strides_and_no_scale():
+def test_two_boolean_operands(family):
+    """No sign plane on either side: the product counts the positions where both bits are set."""
+    a, b = _operands(750, 2, 70, 130, 300, a_bool=True)
+    b = (b != 0).astype(np.int8)
+    assert _run(a, b, synth.scales(750, 1, 1), None, 0.5, True, b_bool=True)
+
+
+def test_vector_scales_strides_and_no_scale(family):
     q, k = _operands(800, 2, 37, 50, 160, a_bool=False)
     s_q, s_k = synth.scales(800, 1, 2 * 37), synth.scales(800, 2, 2 * 50)
     assert _run(q, k, s_q, s_k, 0.125, False, pad_a=8, pad_b=12, ldo=56, pad_out=24)
@@ -127,7 +157,7 @@ def test_vector_scales_strides_and_no_scale():
     assert _run(q, k, None, s_k, 3.0, False)
 
 
-def test_attention_head_shapes_full_size():
+def test_attention_head_shapes_full_size(family):
     """The paper's attention shapes for a 7B-class block: 2048 tokens, head dimension 128."""
     S, D, heads = 2048, 128, 2
     _say("full-size heads", S, D, heads)

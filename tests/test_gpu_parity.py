@@ -52,6 +52,23 @@ def test_quantize_pack_fp16_matches_oracle(M, K, lda):
         assert np.array_equal(w, g), name
 
 
+@pytest.mark.parametrize("M,K,lda", [(2100, 4096, None), (2300, 3720, 3728), (70000, 128, None)])
+def test_quantize_pack_fp16_large_aligned_rows(M, K, lda):
+    """Sizes at which aligned fp16 rows take the four-groups-per-thread kernel: whole rows, rows with
+    padding groups past K, rows narrower than a wavefront's span; a few invalid scales among them."""
+    _say("quantize fp16 large", M, K, lda)
+    A, s = _activation_case(300 + K, M, K, lda)
+    s[5], s[17], s[M - 1] = 0.0, np.nan, np.inf
+    want = oracle.pack_act(oracle.ternarize(np.ascontiguousarray(A[:, :K]), s))
+    got = gpu_quantize_pack(A, s, K=K)
+    for w, g, name in zip(want, got, ("mask", "sign", "nnz")):
+        assert np.array_equal(w, g), name
+    sc = np.array([0.75], np.float16)                                  # one scale for the whole tensor
+    want = oracle.pack_act(oracle.ternarize(np.ascontiguousarray(A[:, :K]), sc))
+    got = gpu_quantize_pack(A, sc, K=K)
+    assert all(np.array_equal(w, g) for w, g in zip(want, got))
+
+
 def test_quantize_pack_scale_modes_and_bad_scales():
     M, K = 9, 200
     A, _ = _activation_case(7, M, K)
