@@ -149,6 +149,23 @@ def test_two_boolean_operands(family):
     assert _run(a, b, synth.scales(750, 1, 1), None, 0.5, True, b_bool=True)
 
 
+def test_products_seeded_random_shapes(family):
+    """Twelve products with shapes, sparsities and operand kinds drawn from a seeded generator:
+    ragged tiles in both directions, K tails inside and across the 256-k slabs."""
+    rng = np.random.default_rng(20260404)
+    for case in range(12):
+        batch, M, N = int(rng.integers(1, 4)), int(rng.integers(1, 300)), int(rng.integers(1, 300))
+        K = int(rng.integers(1, 1500))
+        a_bool, b_bool = bool(rng.integers(0, 2)), bool(rng.integers(0, 4) == 0)
+        _say("tt random", case, batch, M, N, K, a_bool, b_bool)
+        a, b = _operands(5000 + case, batch, M, N, K, a_bool, p0a=float(rng.uniform(0.2, 0.9)))
+        if b_bool:
+            b = (b != 0).astype(np.int8)
+        s_a = synth.scales(5000 + case, 3, batch * M) if case % 2 else synth.scales(5000 + case, 3, 1)
+        s_b = synth.scales(5000 + case, 4, batch * N) if case % 3 == 0 else None
+        assert _run(a, b, s_a, s_b, float(rng.uniform(0.05, 2.0)), a_bool, b_bool=b_bool, dirty=not (a_bool or b_bool))
+
+
 def test_vector_scales_strides_and_no_scale(family):
     q, k = _operands(800, 2, 37, 50, 160, a_bool=False)
     s_q, s_k = synth.scales(800, 1, 2 * 37), synth.scales(800, 2, 2 * 50)

@@ -202,6 +202,23 @@ def test_matrix_core_decode_every_work_split(rpw, tiles, pf):
         B.set_tile(0)
 
 
+def test_decode_seeded_random_shapes():
+    """Twenty decode-sized problems with shapes drawn from a seeded generator (token counts across
+    the token-group boundaries, ragged channel counts, K tails anywhere inside a 512-k chunk), on
+    both decode kernel families and the dispatcher's choice."""
+    rng = np.random.default_rng(20260403)
+    for case in range(20):
+        M = int(rng.choice([1, 2, 3, 5, 8, 15, 16, 17, 31, 33, 48, 63, 64]))
+        N = int(rng.integers(1, 700))
+        K = int(rng.integers(1, 9000))
+        _say("decode random", case, M, N, K)
+        t, w, s_a, s_w = _gemm_case(4000 + case, M, N, K, p0=float(rng.uniform(0.1, 0.9)))
+        assert _check_gemm(t, w, s_a, s_w, B.PATH_AUTO, dirty_sign=True)
+        assert _check_gemm(t, w, s_a, s_w, B.PATH_FP4)
+        if M <= 16:
+            assert _check_gemm(t, w, s_a, s_w, B.PATH_POPC)
+
+
 @pytest.mark.parametrize("path", PATHS)
 def test_gemm_config1_tiny(path):
     c = synth.config1()
