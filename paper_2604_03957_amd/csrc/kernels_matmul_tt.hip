@@ -13,6 +13,8 @@
 // bit planes in HBM and LDS and are expanded to nibbles in registers.  k_matmul_tt is the vector-ALU
 // form (LDS-tiled, wave64: per 32 multiply-accumulates one AND, one three-input boolean op and two
 // popcount-accumulates), kept as the comparison path.
+#include <type_traits>
+
 #include "bwta_internal.h"
 
 namespace bwta {
@@ -235,20 +237,46 @@ __global__ __launch_bounds__(256, 2) void k_matmul_tt_fp4(MatmulTTArgs g)
             for (int v = 0; v < 16; ++v) acc[j][i][v] = 0.0f;
 
     const int nslab = (rw + FSW - 1) / FSW;
-    auto compute = [&](int buf) {
+    // A full slab: lane (r32, h) takes words 4 h .. 4 h + 3 of its row, one per step.  A last slab
+    // that holds only four words (K = 128: the whole row) deals them as words 2 h, 2 h + 1 over two
+    // steps instead, so no instruction runs on an operand half made of padding.
+    auto compute = [&](int buf, auto half_slab) {
+        constexpr bool HALF = decltype(half_slab)::value;
+        constexpr int NS = HALF ? 2 : 4;
         const uint32_t *st = fsm + buf * FSTAGE;
-        v4u am[2], as[2], bm[2], bs[2];
+        uint32_t am[2][NS], as[2][NS], bm[2][NS], bs[2][NS];
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            const int ra = (wm * 64 + 32 * i + r32) * FPITCH + 4 * h, rb = (wn * 64 + 32 * i + r32) * FPITCH + 4 * h;
-            am[i] = *(const v4u *)(st + ra);
-            if (SIGN_A) as[i] = *(const v4u *)(st + FPLANE + ra);
-            bm[i] = *(const v4u *)(st + 2 * FPLANE + rb);
-            if (SIGN_B) bs[i] = *(const v4u *)(st + 3 * FPLANE + rb);
-        }
-        // a last slab with fewer than 8 words still takes all four steps: its missing words are zero
+            const int ra = (wm * 64 + 32 * i + r32) * FPITCH + NS * h, rb = (wn * 64 + 32 * i + r32) * FPITCH + NS * h;
+            if (HALF) {
+                const uint2 a0 = *(const uint2 *)(st + ra), b0 = *(const uint2 *)(st + 2 * FPLANE + rb);
+                am[i][0] = a0.x, am[i][1] = a0.y, bm[i][0] = b0.x, bm[i][1] = b0.y;
+                if (SIGN_A) {
+                    const uint2 a1 = *(const uint2 *)(st + FPLANE + ra);
+                    as[i][0] = a1.x, as[i][1] = a1.y;
+                }
+                if (SIGN_B) {
+                    const uint2 b1 = *(const uint2 *)(st + 3 * FPLANE + rb);
+                    bs[i][0] = b1.x, bs[i][1] = b1.y;
+                }
+            } else {
+                const v4u a0 = *(const v4u *)(st + ra), b0 = *(const v4u *)(st + 2 * FPLANE + rb);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
+                for (int s = 0; s < NS; ++s) am[i][s] = a0[s], bm[i][s] = b0[s];
+                if (SIGN_A) {
+                    const v4u a1 = *(const v4u *)(st + FPLANE + ra);
+#pragma unroll
+                    for (int s = 0; s < NS; ++s) as[i][s] = a1[s];
+                }
+                if (SIGN_B) {
+                    const v4u b1 = *(const v4u *)(st + 3 * FPLANE + rb);
+#pragma unroll
+                    for (int s = 0; s < NS; ++s) bs[i][s] = b1[s];
+                }
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
             v8i fa[2], fb[2];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
@@ -272,13 +300,18 @@ __global__ __launch_bounds__(256, 2) void k_matmul_tt_fp4(MatmulTTArgs g)
     sc_lds[tid] = have ? half_bits_to_float(sc_bits) : (want ? 1.0f : 0.0f);
     __syncthreads();
     int buf = 0;
-    for (int it = 0; it < nslab; ++it) {
+    const int nfull = rw / FSW;  // rw is a multiple of 4: what is left after the full slabs is one half slab
+    for (int it = 0; it < nfull; ++it) {
         const int nxt = it + 1 < nslab ? it + 1 : nslab - 1;
         fetch(nxt, pre);
-        compute(buf);
+        compute(buf, std::false_type{});
         stage(buf ^ 1, nxt, pre);
         __syncthreads();
         buf ^= 1;
+    }
+    if (nfull < nslab) {  // staged by the last iteration (or by the prologue when it is the only slab)
+        compute(buf, std::true_type{});
+        __syncthreads();  // the epilogue's strips reuse the slab memory
     }
 
     // ---- epilogue.  Lane (r32, h) of block (j, i) holds m = 32 i + r32 and n = 32 j + 8 q + 4 h + e
