@@ -160,7 +160,6 @@ int bwta_gemm_grouped(const bwta_gemm_problem *problems, int count, int M, int N
                       int a_scale_mode, int w_scale_mode, int64_t ldo, void *workspace,
                       size_t workspace_bytes, bwta_stream_t stream);
 
-/* Human-readable text for a return code (static storage). */
 /*
  * Boolean activations (the paper's bool function, used for attention probabilities and other
  * non-negative activations): bit k of word k / 32 of row m = 1 iff A[m, k] >= 0.5 * s (exact
@@ -215,6 +214,7 @@ int bwta_prepare_weights(const void *W, int64_t ldw, int N, int K, uint32_t *wsi
  */
 int bwta_act_scale(const void *A, int64_t lda, int M, int K, void *s, bwta_stream_t stream);
 
+/* Human-readable text for a return code (static storage). */
 const char *bwta_strerror(int code);
 /* hipError_t value behind the calling thread's most recent BWTA_ERR_HIP (0 if none). */
 int bwta_last_hip_error(void);
@@ -224,10 +224,11 @@ int bwta_get_path(void);
 /* Which family AUTO resolves to for a shape: BWTA_PATH_POPC, BWTA_PATH_MFMA or BWTA_PATH_FP4. */
 int bwta_auto_path(int M, int N, int K);
 /* Tuning hook for benchmark sweeps: force the FP4 kernel's per-wavefront tile (22, 21, 12, 11 =
- * blocks of 32 rows x 32 columns per wavefront; 23 = 22 at three wavefronts per SIMD), the popcount decode kernel's row split (1000 +
- * 16 * lanes per row + chunks per lane) or the matrix-core decode kernel's work split (2000 +
- * 1024 * ring depth + 64 * chunks per wavefront + tiles per workgroup); 0 restores the built-in
- * choices.  Results do not depend on it. */
+ * blocks of 32 rows x 32 columns per wavefront; 23 = 22 at three wavefronts per SIMD), the
+ * popcount decode kernel's row split (1000 + 16 * lanes per row + chunks per lane) or the
+ * matrix-core decode kernel's work split (2000 + 1024 * ring depth (2..4) + 64 * chunks per
+ * wavefront (1..4) + tiles per workgroup (rounded up to a multiple of the ring depth, fewer if LDS
+ * does not hold their partials)); 0 restores the built-in choices.  Results do not depend on it. */
 int bwta_set_tile(int tile);
 /* Library version, major * 100 + minor. */
 int bwta_version(void);
