@@ -10,7 +10,7 @@ layers.  Inputs are resident in HBM before the timed region; weights are packed 
 Prints ONE JSON line.  `value` is effective TOPS = 2*M*N*K summed over the step / time
 (zeros counted, dense-equivalent work).  `roofline` is for the dominant kernel, timed live
 with HIP events on the launch stream; `cpu_baseline` is the CPU oracle timed on the host
-cores of the same box.  Other workloads: --workload c1_tiny | c3_prefill | c4_decode | c5_block | attn | copy_probe.
+cores of the same box.  Other workloads: --workload c1_tiny | c3_prefill | c4_decode | c5_block | attn | prep | copy_probe.
 """
 import argparse
 import json
@@ -478,6 +478,31 @@ def run_c5(args, torch, B, synth):
                                 "RMSNorm, SiLU, residuals and the four per-token scale kernels (bwta_act_scale)"}}
 
 
+def run_prep(args, torch, B, synth):
+    """Weight preparation from an fp16 matrix (centre, sign-pack, per-channel scale) and the per-token
+    activation-scale statistic, at the decoder block's largest shapes; both read their input once."""
+    dev = "cuda:0"
+    N, K, M = 4096, 11008, 2048
+    W = _dev((synth.gaussian(7, 1, N * K) * 0.02).astype(np.float16).reshape(N, K), torch)
+    A = _dev(synth.laplace_activations(7, 2, M, K), torch)
+    wsign = torch.empty((N, B.plane_row_words(K)), dtype=torch.int32, device=dev)
+    s_w = torch.empty((N,), dtype=torch.float16, device=dev)
+    s_a = torch.empty((M,), dtype=torch.float16, device=dev)
+    steps = max(5, args.steps // 10)
+    tw = _event_ms(torch, lambda: B.bwta_prepare_weights(W, wsign, s_w, N=N, K=K), steps, 2)
+    ta = _event_ms(torch, lambda: B.bwta_act_scale(A, s_a, M=M, K=K), steps, 2)
+    bw = (2.0 * N * K + N * K / 8 + 2 * N) / (tw * 1e-3) / 1e9
+    ba = (2.0 * M * K + 2 * M) / (ta * 1e-3) / 1e9
+    return {"metric": "BWTA weight preparation achieved HBM GB/s", "value": round(bw, 1), "unit": "GB/s", "n_gpus": 1,
+            "steps": steps, "warmup": 2, "ms_per_step": round(tw, 5), "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "int64 (exact row sums of fp16 values)", "data": "synthetic",
+            "config": {"workload": "prep: bwta_prepare_weights on fp16 [4096,11008], bwta_act_scale on fp16 [2048,11008]"},
+            "roofline": {"bound": "hbm", "kernel": "k_prepare_weights", "achieved": round(bw, 1), "peak": PEAK_HBM_GBS,
+                         "unit": "GB/s", "frac": round(bw / PEAK_HBM_GBS, 4), "traffic": None},
+            "kernels": {"prepare_weights_us": round(tw * 1e3, 1), "prepare_weights_GBs": round(bw, 1),
+                        "act_scale_us": round(ta * 1e3, 1), "act_scale_GBs": round(ba, 1)}}
+
+
 def run_copy_probe(args, torch, B, synth):
     """A plain device-to-device copy of known size (256 MiB), used to calibrate the FETCH_SIZE /
     WRITE_SIZE counters that the traffic figures in profiles/ are scaled by."""
@@ -497,7 +522,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c2_ffn", choices=["c2_ffn", "c1_tiny", "c3_prefill", "c4_decode", "c5_block", "attn", "copy_probe"])
+    ap.add_argument("--workload", default="c2_ffn", choices=["c2_ffn", "c1_tiny", "c3_prefill", "c4_decode", "c5_block", "attn", "prep", "copy_probe"])
     ap.add_argument("--decode-matrices", type=int, default=64)
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--graph", action="store_true",
@@ -516,7 +541,7 @@ def main():
     from paper_2604_03957_amd import synth
     torch.cuda.set_device(0)
     run = {"c2_ffn": run_c2, "c1_tiny": run_c1, "c3_prefill": run_c3, "c4_decode": run_c4,
-           "c5_block": run_c5, "attn": run_attn, "copy_probe": run_copy_probe}[args.workload]
+           "c5_block": run_c5, "attn": run_attn, "prep": run_prep, "copy_probe": run_copy_probe}[args.workload]
     out = run(args, torch, B, synth)
     print(json.dumps(out), flush=True)
 

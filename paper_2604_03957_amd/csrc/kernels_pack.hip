@@ -226,16 +226,6 @@ __global__ __launch_bounds__(kThreads) void k_row_popcount(const uint32_t *__res
 // integer whatever the order of the additions, and "W[n,k] - mean >= 0" is the integer test
 // K * W[n,k] >= sum.  Every discrete decision is therefore identical to exact arithmetic.
 
-// finite binary16 -> integer count of 2^-24; NaN / Inf -> 0 with *finite = false
-__device__ __forceinline__ long long half_fixed(uint16_t h, bool *finite)
-{
-    const int expo = (h >> 10) & 0x1f, frac = h & 0x3ff;
-    *finite = expo != 31;
-    long long v = expo == 0 ? (long long)frac : ((long long)(1024 + frac) << (expo - 1));
-    if (expo == 31) v = 0;
-    return (h & 0x8000) ? -v : v;
-}
-
 // non-negative double -> binary16 bits, round to nearest even, straight from the 53-bit significand
 // (going through fp32 would round twice)
 __device__ __forceinline__ uint16_t double_to_half_bits(double x)
@@ -259,8 +249,8 @@ __device__ __forceinline__ uint16_t double_to_half_bits(double x)
     return (uint16_t)(((e + 15) << 10) | (int)(q - 1024));
 }
 
-template <typename T>
-__device__ __forceinline__ T block_sum(T v, T *scratch /* [kThreads / 64] */)
+template <int NT, typename T>
+__device__ __forceinline__ T block_sum(T v, T *scratch /* [NT / 64] */)
 {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
@@ -269,7 +259,7 @@ __device__ __forceinline__ T block_sum(T v, T *scratch /* [kThreads / 64] */)
     __syncthreads();
     T r = scratch[0];
 #pragma unroll
-    for (int i = 1; i < kThreads / 64; ++i) r += scratch[i];
+    for (int i = 1; i < NT / 64; ++i) r += scratch[i];
     return r;
 }
 
@@ -285,75 +275,178 @@ __device__ __forceinline__ void load8_halfs(const uint16_t *row, int k0, int nva
     }
 }
 
-// One workgroup per output channel: mean (exact), sign(W - mean) packed like bwta_pack_weights,
-// s_w = mean |W - mean| (sum of exact integers |K W - sum| in double, one division, one rounding).
-__global__ __launch_bounds__(kThreads) void k_prepare_weights(const uint16_t *__restrict__ W, int64_t ldw, int K,
-                                                              int rw, uint32_t *__restrict__ wsign,
-                                                              uint16_t *__restrict__ s_w, int vec_ok)
+// two sums at once (one pair of barriers); every thread gets both
+template <int NT>
+__device__ __forceinline__ void block_sum2(long long &a, long long &b, long long *scratch /* [2 * NT / 64] */)
 {
-    __shared__ long long s_ll[kThreads / 64];
-    __shared__ double s_d[kThreads / 64];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        a += __shfl_xor(a, off);
+        b += __shfl_xor(b, off);
+    }
+    __syncthreads();  // scratch may still be read from a previous call
+    if ((threadIdx.x & 63) == 0) {
+        scratch[2 * (threadIdx.x >> 6)] = a;
+        scratch[2 * (threadIdx.x >> 6) + 1] = b;
+    }
+    __syncthreads();
+    a = scratch[0], b = scratch[1];
+#pragma unroll
+    for (int i = 1; i < NT / 64; ++i) a += scratch[2 * i], b += scratch[2 * i + 1];
+}
+
+// The row of a workgroup of NT threads, 8 halfs per 128-bit register, NG registers per thread (group g
+// of thread t is byte-group t + NT g).  Few, long-lived wavefronts per row: the reductions, the
+// division and the bound are a fixed cost per wavefront that dwarfs the per-element work.  All requests go out before the first value is used; the second
+// pass of the weight preparation reads the registers, not memory.  Padding and out-of-row groups
+// read as +0 (and are kept out of every count by nvalid).
+template <int NG, int NT>
+__device__ __forceinline__ void load_row_groups(const uint16_t *row, int K, int c8, bool whole, uint4 (&x)[NG])
+{
+    if (whole) {  // 16-byte aligned rows, K a multiple of 8: every group is whole or absent
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            const int k0 = 8 * ((int)threadIdx.x + NT * g);
+            x[g] = *(const uint4 *)(k0 < K ? row + k0 : row);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int g = 0; g < NG; ++g)
+            if (8 * ((int)threadIdx.x + NT * g) >= K) x[g] = make_uint4(0, 0, 0, 0);
+    } else {
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            const int c = (int)threadIdx.x + NT * g, k0 = 8 * c;
+            const int nvalid = c < c8 ? (K - k0 >= 8 ? 8 : (K - k0 > 0 ? K - k0 : 0)) : 0;
+            uint16_t v[8];
+            load8_halfs(row, k0, nvalid, false, v);
+            x[g] = make_uint4(v[0] | ((uint32_t)v[1] << 16), v[2] | ((uint32_t)v[3] << 16),
+                              v[4] | ((uint32_t)v[5] << 16), v[6] | ((uint32_t)v[7] << 16));
+        }
+    }
+}
+
+__device__ __forceinline__ uint16_t half_of(const uint4 &q, int i)
+{
+    const uint32_t w = i < 2 ? q.x : (i < 4 ? q.y : (i < 6 ? q.z : q.w));
+    return (uint16_t)(w >> (16 * (i & 1)));
+}
+
+// A per-thread sum of at most 128 finite binary16 values is a multiple of 2^-24 below 2^23: exact
+// in a double whatever the order.  This turns it into the integer count of 2^-24.
+__device__ __forceinline__ long long double_units(double s) { return (long long)(s * 16777216.0); }
+
+// The smallest value on the binary16 grid that is >= c * 2^-24 (c an integer count of 2^-24), as a
+// float; +Inf if there is none.  For every finite binary16 x with integer count X:
+// X >= c  <=>  float(x) >= result, so a 64-bit comparison per element becomes one float compare.
+__device__ __forceinline__ float half_grid_ceil(long long c)
+{
+    const long long top = 65504ll << 24;
+    if (c > top) return __builtin_inff();
+    const bool negative = c < 0;
+    unsigned long long a = (unsigned long long)(negative ? -c : c);
+    if (a > (unsigned long long)top) a = (unsigned long long)top;  // only for c < -top: every finite x is >= c
+    const int p = 63 - __builtin_clzll(a | 1ull);                   // position of the leading one
+    if (p > 10) {  // grid spacing 2^(p-10): magnitudes round down for a negative bound, up for a positive one
+        const unsigned long long sp = 1ull << (p - 10);
+        a = negative ? (a & ~(sp - 1)) : ((a + sp - 1) & ~(sp - 1));
+    }
+    const float v = (float)(long long)a * 5.9604644775390625e-08f;  // at most 12 significant bits: exact
+    return negative ? -v : v;
+}
+
+// One workgroup per output channel: mean (exact), sign(W - mean) packed like bwta_pack_weights,
+// s_w = mean |W - mean|.  With X the integer count of 2^-24 of an element and S the row's exact sum,
+// "W - mean < 0" is X K < S, i.e. X < ceil(S / K): one float compare against the bound above.  The
+// sum of |X K - S| over the finite elements equals K (S - 2 Sn) - S (n - 2 nn) with Sn, nn the sum
+// and count of the finite elements below the mean and n the count of finite elements, so the second
+// pass needs only exact per-thread sums again; the final combination is done in double (one
+// division, one rounding to binary16).
+template <int NG, int NT>
+__global__ __launch_bounds__(NT) void k_prepare_weights(const uint16_t *__restrict__ W, int64_t ldw, int K,
+                                                              int rw, uint32_t *__restrict__ wsign,
+                                                              uint16_t *__restrict__ s_w, int whole)
+{
+    __shared__ long long s_ll[2 * NT / 64];
+    __shared__ float s_bound;
     const int n = blockIdx.x, c8 = rw * 4, lane = threadIdx.x & 63;
-    const uint16_t *row = W + (int64_t)n * ldw;
-    long long part = 0;
-    for (int c = threadIdx.x; c < c8; c += kThreads) {
-        const int k0 = c * 8, nvalid = K - k0 >= 8 ? 8 : (K - k0 > 0 ? K - k0 : 0);
-        uint16_t v[8];
-        load8_halfs(row, k0, nvalid, vec_ok, v);
+    uint4 x[NG];
+    load_row_groups<NG, NT>(W + (int64_t)n * ldw, K, c8, whole != 0, x);
+
+    double part = 0.0;
+    int nfin = 0;
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {  // elements past K were loaded as +0: finite, and they add nothing
+            const uint16_t h = half_of(x[g], i);
+            const bool fin = (h & 0x7c00) != 0x7c00;
+            part += (double)(fin ? half_bits_to_float(h) : 0.0f);
+            nfin += fin ? 0 : 1;  // counts the non-finite ones
+        }
+    }
+    long long S = double_units(part), NF = nfin;
+    block_sum2<NT>(S, NF, s_ll);
+    NF = K - NF;  // finite elements of the row
+    if (threadIdx.x == 0) {  // one 64-bit division per row, not per wavefront
+        const long long q = S / K, r = S - q * K;
+        s_bound = half_grid_ceil(q + (r > 0 ? 1 : 0));  // ceil(S / K)
+    }
+    __syncthreads();
+    const float bound = s_bound;
+    // The second pass recomputes its per-element predicates from the registers: kept opaque here,
+    // or the compiler carries 64 of them per thread across the barriers in spilled scalar registers.
+#pragma unroll
+    for (int g = 0; g < NG; ++g) asm volatile("" : "+v"(x[g].x), "+v"(x[g].y), "+v"(x[g].z), "+v"(x[g].w));
+
+    double below = 0.0;
+    int nbelow = 0;
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+        const int c = (int)threadIdx.x + NT * g, k0 = 8 * c;
+        uint32_t bits = 0;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            bool fin;
-            part += half_fixed(v[i], &fin);  // padding reads as +0
+            const uint16_t h = half_of(x[g], i);
+            const float f = half_bits_to_float(h);
+            const bool inside = k0 + i < K;
+            const bool neg = inside && !(f >= bound);  // NaN and -Inf -> -1, +Inf -> +1
+            const bool fin_neg = neg && (h & 0x7c00) != 0x7c00;
+            bits |= (uint32_t)neg << i;
+            below += (double)(fin_neg ? f : 0.0f);
+            nbelow += fin_neg ? 1 : 0;
         }
-    }
-    const long long S = block_sum(part, s_ll);
-    double tpart = 0.0;
-    for (int c0 = 0; c0 < c8; c0 += kThreads) {  // whole quads stay together for quad_word
-        const int c = c0 + threadIdx.x;
-        uint32_t bits = 0;
-        if (c < c8) {
-            const int k0 = c * 8, nvalid = K - k0 >= 8 ? 8 : (K - k0 > 0 ? K - k0 : 0);
-            uint16_t v[8];
-            load8_halfs(row, k0, nvalid, vec_ok, v);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                bool fin;
-                const long long x = half_fixed(v[i], &fin);
-                const long long d = x * K - S;  // |x K| < 2^40 * 2^15
-                const bool neg = fin ? d < 0 : v[i] != 0x7c00;  // -Inf and NaN -> -1, +Inf -> +1
-                if (i < nvalid) {
-                    bits |= (uint32_t)neg << i;
-                    if (fin) tpart += (double)(d < 0 ? -d : d);
-                }
-            }
-        }
-        const uint32_t word = quad_word(bits, lane);
+        const uint32_t word = quad_word(bits, lane);  // whole quads stay together: c8 is a multiple of 4
         if (c < c8 && (lane & 3) == 0) wsign[(int64_t)n * rw + (c >> 2)] = word;
     }
-    const double T = block_sum(tpart, s_d);
-    if (threadIdx.x == 0) s_w[n] = double_to_half_bits(T / ((double)K * (double)K * 16777216.0));
+    long long SN = double_units(below), NN = nbelow;
+    block_sum2<NT>(SN, NN, s_ll);
+    if (threadIdx.x == 0) {
+        const double T = (double)K * (double)(S - 2 * SN) - (double)S * (double)(NF - 2 * NN);
+        s_w[n] = double_to_half_bits(T / ((double)K * (double)K * 16777216.0));
+    }
 }
 
 // One workgroup per token: s[m] = 2 * mean_k |A[m, k]| (exact integer sum, one division, one rounding).
-__global__ __launch_bounds__(kThreads) void k_act_scale(const uint16_t *__restrict__ A, int64_t lda, int K,
-                                                        uint16_t *__restrict__ s, int vec_ok)
+template <int NG, int NT>
+__global__ __launch_bounds__(NT) void k_act_scale(const uint16_t *__restrict__ A, int64_t lda, int K,
+                                                        uint16_t *__restrict__ s, int whole)
 {
-    __shared__ long long s_ll[kThreads / 64];
+    __shared__ long long s_ll[NT / 64];
     const int m = blockIdx.x, c8 = (K + 7) / 8;
-    const uint16_t *row = A + (int64_t)m * lda;
-    long long part = 0;
-    for (int c = threadIdx.x; c < c8; c += kThreads) {
-        const int k0 = c * 8, nvalid = K - k0 >= 8 ? 8 : K - k0;
-        uint16_t v[8];
-        load8_halfs(row, k0, nvalid, vec_ok, v);
+    uint4 x[NG];
+    load_row_groups<NG, NT>(A + (int64_t)m * lda, K, c8, whole != 0, x);
+    double part = 0.0;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            bool fin;
-            const long long x = half_fixed(v[i], &fin);
-            part += x < 0 ? -x : x;
+    for (int g = 0; g < NG; ++g) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {  // elements past K were loaded as +0 and add nothing
+            const uint16_t h = half_of(x[g], i) & 0x7fff;
+            const float f = h < 0x7c00 ? half_bits_to_float(h) : 0.0f;  // NaN / Inf stay out
+            part += (double)f;
         }
     }
-    const long long S = block_sum(part, s_ll);
+    const long long S = block_sum<NT>(double_units(part), s_ll);
     if (threadIdx.x == 0) s[m] = double_to_half_bits((double)S / ((double)K * 8388608.0));  // 2 S / (K 2^24)
 }
 
@@ -383,18 +476,32 @@ hipError_t launch_prepare_weights(const void *W, int64_t ldw, int N, int K, uint
 {
     if (N == 0) return hipSuccess;
     const int rw = 4 * ((K + 127) / 128);
-    const int vec_ok = (((uintptr_t)W % 16) == 0 && (ldw % 8) == 0) ? 1 : 0;
-    hipLaunchKernelGGL(k_prepare_weights, dim3(N), dim3(kThreads), 0, st, (const uint16_t *)W, ldw, K, rw, wsign, s_w,
-                       vec_ok);
-    return hipGetLastError();
+    const int whole = (((uintptr_t)W % 16) == 0 && (ldw % 8) == 0 && (K % 8) == 0) ? 1 : 0;
+    const int c8 = rw * 4;  // 128-bit groups per row; K <= 32768 -> at most 4096
+#define BWTA_PREP(NG_, NT_)                                                                                   \
+    if (c8 <= NG_ * NT_) {                                                                                    \
+        hipLaunchKernelGGL((k_prepare_weights<NG_, NT_>), dim3(N), dim3(NT_), 0, st, (const uint16_t *)W, ldw, K, rw, \
+                           wsign, s_w, whole);                                                                \
+        return hipGetLastError();                                                                             \
+    }
+    BWTA_PREP(1, 256) BWTA_PREP(2, 256) BWTA_PREP(4, 256) BWTA_PREP(8, 256) BWTA_PREP(4, 1024)
+#undef BWTA_PREP
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_act_scale(const void *A, int64_t lda, int M, int K, uint16_t *s, hipStream_t st)
 {
     if (M == 0) return hipSuccess;
-    const int vec_ok = (((uintptr_t)A % 16) == 0 && (lda % 8) == 0) ? 1 : 0;
-    hipLaunchKernelGGL(k_act_scale, dim3(M), dim3(kThreads), 0, st, (const uint16_t *)A, lda, K, s, vec_ok);
-    return hipGetLastError();
+    const int whole = (((uintptr_t)A % 16) == 0 && (lda % 8) == 0 && (K % 8) == 0) ? 1 : 0;
+    const int c8 = (K + 7) / 8;
+#define BWTA_SCALE(NG_, NT_)                                                                                       \
+    if (c8 <= NG_ * NT_) {                                                                                         \
+        hipLaunchKernelGGL((k_act_scale<NG_, NT_>), dim3(M), dim3(NT_), 0, st, (const uint16_t *)A, lda, K, s, whole); \
+        return hipGetLastError();                                                                                  \
+    }
+    BWTA_SCALE(1, 256) BWTA_SCALE(2, 256) BWTA_SCALE(4, 256) BWTA_SCALE(8, 256) BWTA_SCALE(4, 1024)
+#undef BWTA_SCALE
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_quantize_pack(const void *A, int dtype, int64_t lda, ScaleArg s_a, int M, int K,
