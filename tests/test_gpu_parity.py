@@ -244,8 +244,8 @@ def test_gemm_degenerate_inputs(path):
 
 
 @pytest.mark.parametrize("path", PATHS)
-def test_gemm_output_selection_and_scale_modes(path):
-    M, N, K = 20, 36, 256
+@pytest.mark.parametrize("M,N,K", [(20, 36, 256), (200, 130, 600)])  # decode kernels / tiled kernels
+def test_gemm_output_selection_and_scale_modes(path, M, N, K):
     t, w, s_a, s_w = _gemm_case(5, M, N, K)
     mask, sign, _ = oracle.pack_act(t)
     ws = oracle.pack_weights(w)
