@@ -340,42 +340,58 @@ __global__ __launch_bounds__(256, 2) void k_matmul_tt_fp4(MatmulTTArgs g)
     const float *sb_lds = sc_lds, *sa_lds = sc_lds + FT;
     const bool full = (m_wave + 64 <= g.M) && (n_wave + 64 <= g.N) && ((g.ldo & 7) == 0) &&
                       (g.batch == 1 || (g.stride_out & 7) == 0) && (((uintptr_t)g.out & 15) == 0);
+    // Layerwise (scalar or absent) scales on both sides make the factor one number for the whole
+    // launch; per-row scales cost two multiplications per element, which is what bounds Q K^T.
+    const bool one_factor = sa.mode != 2 && sb.mode != 2;
+    const float factor = g.alpha * (sa_lds[0] * sb_lds[0]);  // row m0 and column n0 exist
+    auto write_out = [&](auto uniform) {
+        constexpr bool UNI = decltype(uniform)::value;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const float fa = sa_lds[wm * 64 + 32 * i + r32];
+        for (int i = 0; i < 2; ++i) {
+            const float fa = sa_lds[wm * 64 + 32 * i + r32];
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
+            for (int j = 0; j < 2; ++j) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int nl = 32 * j + 8 * q + 4 * h;
-                const float4 fb = *(const float4 *)(sb_lds + wn * 64 + nl);
-                uint2 hv;
-                hv.x = scaled_to_half2(acc[j][i][4 * q], g.alpha * (fa * fb.x), acc[j][i][4 * q + 1], g.alpha * (fa * fb.y));
-                hv.y = scaled_to_half2(acc[j][i][4 * q + 2], g.alpha * (fa * fb.z), acc[j][i][4 * q + 3], g.alpha * (fa * fb.w));
-                *(uint2 *)(strip + r32 * FSTRIP_PITCH + nl) = hv;
+                for (int q = 0; q < 4; ++q) {
+                    const int nl = 32 * j + 8 * q + 4 * h;
+                    float s0 = factor, s1 = factor, s2 = factor, s3 = factor;
+                    if (!UNI) {
+                        const float4 fb = *(const float4 *)(sb_lds + wn * 64 + nl);
+                        s0 = g.alpha * (fa * fb.x), s1 = g.alpha * (fa * fb.y);
+                        s2 = g.alpha * (fa * fb.z), s3 = g.alpha * (fa * fb.w);
+                    }
+                    uint2 hv;
+                    hv.x = scaled_to_half2(acc[j][i][4 * q], s0, acc[j][i][4 * q + 1], s1);
+                    hv.y = scaled_to_half2(acc[j][i][4 * q + 2], s2, acc[j][i][4 * q + 3], s3);
+                    *(uint2 *)(strip + r32 * FSTRIP_PITCH + nl) = hv;
+                }
             }
-        }
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
 #pragma unroll
-        for (int rr = 0; rr < 32; rr += 8) {
-            const int row = rr + (lane >> 3), c8 = 8 * (lane & 7);
-            const int mo = m_wave + 32 * i + row, n = n_wave + c8;
-            const uint4 qd = *(const uint4 *)(strip + row * FSTRIP_PITCH + c8);
-            uint16_t *dst = out + (int64_t)mo * g.ldo + n;
-            if (full) {
-                const v4u qv = {qd.x, qd.y, qd.z, qd.w};
-                __builtin_nontemporal_store(qv, (v4u *)dst);  // streamed once, never re-read here
-            } else if (mo < g.M && n < g.N) {
-                const uint32_t w[4] = {qd.x, qd.y, qd.z, qd.w};
+            for (int rr = 0; rr < 32; rr += 8) {
+                const int row = rr + (lane >> 3), c8 = 8 * (lane & 7);
+                const int mo = m_wave + 32 * i + row, n = n_wave + c8;
+                const uint4 qd = *(const uint4 *)(strip + row * FSTRIP_PITCH + c8);
+                uint16_t *dst = out + (int64_t)mo * g.ldo + n;
+                if (full) {
+                    const v4u qv = {qd.x, qd.y, qd.z, qd.w};
+                    __builtin_nontemporal_store(qv, (v4u *)dst);  // streamed once, never re-read here
+                } else if (mo < g.M && n < g.N) {
+                    const uint32_t w[4] = {qd.x, qd.y, qd.z, qd.w};
 #pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if (n + e < g.N) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+                    for (int e = 0; e < 8; ++e)
+                        if (n + e < g.N) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+                }
             }
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         }
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    }
+    };
+    if (one_factor)
+        write_out(std::true_type{});
+    else
+        write_out(std::false_type{});
 }
 
 template <bool SIGN_A, bool SIGN_B>
