@@ -342,8 +342,9 @@ hipError_t launch_shape(const DecodeBatch &b, int count, DecodeShape sh, hipStre
     if ((chunks + RPW - 1) / RPW > 8 && (chunks + 1) / 2 <= 16) RPW = 2;
     // tiles per workgroup: as many as still leave about 1024 workgroups in the launch
     const int64_t work = (int64_t)tiles * count * ((sh.M + 15) / 16);
-    int T = work >= 8 * 1024 ? 8 : work >= 4 * 1024 ? 4 : 2;
-    int PF = RPW >= 3 ? 2 : T >= 4 ? 4 : 2;
+    // (a single small matrix: one tile per workgroup, so that every compute unit gets one)
+    int T = work >= 8 * 1024 ? 8 : work >= 4 * 1024 ? 4 : work >= 1024 ? 2 : 1;
+    int PF = T == 1 ? 1 : RPW >= 3 ? 2 : T >= 4 ? 4 : 2;
     if (g_force_rpw) {
         if ((chunks + g_force_rpw - 1) / g_force_rpw <= 16) RPW = g_force_rpw;
         if (g_force_t) T = g_force_t;
@@ -355,14 +356,15 @@ hipError_t launch_shape(const DecodeBatch &b, int count, DecodeShape sh, hipStre
     while (decode_lds_bytes(RPW, KW, T) > 64 * 1024 || 16 * T + 16 > 128 * KW) {
         if (T > PF) T -= PF;
         else if (PF > 2) PF = T = 2;
+        else if (PF == 2) PF = T = 1;
         else break;
     }
     sh.T = T;
 #define BWTA_DEC(R_, P_) if (RPW == R_ && PF == P_) return launch_cfg<R_, P_>(b, count, sh, st);
-    BWTA_DEC(1, 2) BWTA_DEC(1, 3) BWTA_DEC(1, 4)
-    BWTA_DEC(2, 2) BWTA_DEC(2, 3) BWTA_DEC(2, 4)
-    BWTA_DEC(3, 2) BWTA_DEC(3, 3)
-    BWTA_DEC(4, 2)  // deeper rings at 3 or 4 chunks per wavefront do not fit 128 registers
+    BWTA_DEC(1, 1) BWTA_DEC(1, 2) BWTA_DEC(1, 3) BWTA_DEC(1, 4)
+    BWTA_DEC(2, 1) BWTA_DEC(2, 2) BWTA_DEC(2, 3) BWTA_DEC(2, 4)
+    BWTA_DEC(3, 1) BWTA_DEC(3, 2) BWTA_DEC(3, 3)
+    BWTA_DEC(4, 1) BWTA_DEC(4, 2)  // deeper rings at 3 or 4 chunks per wavefront do not fit 128 registers
 #undef BWTA_DEC
     return hipErrorInvalidValue;
 }
@@ -408,7 +410,7 @@ void set_gemv_fp4_tile(int rpw, int t, int pf)
 {
     g_force_rpw = rpw;
     g_force_t = t;
-    g_force_pf = (pf >= 2 && pf <= 4) ? pf : 0;
+    g_force_pf = (pf >= 1 && pf <= 4) ? pf : 0;
 }
 
 }  // namespace bwta

@@ -191,10 +191,23 @@ hipError_t launch_t(const GemvBatch &b, int count, const GemvShape &sh, hipStrea
     constexpr int UNR = ROOM >= 4 ? 4 : (ROOM >= 2 ? 2 : 1);
     constexpr int RPP = 64 / G;
     const int64_t passes = ((int64_t)sh.N + RPP - 1) / RPP;
+    const size_t lds = (size_t)sh.M * 2 * sh.C4 * 16;  // <= 8 * 2 * 128 * 16 = 32 KiB
+    const bool nt = (sh.rw & 31) == 0;
+    // A single small matrix: one pass per wavefront, so that every compute unit gets a workgroup
+    // (with 4 passes a 4096-row matrix is 128 workgroups for 256 compute units).
+    if constexpr (MT <= 2 && UNR > 1) {
+        if (((passes + UNR - 1) / UNR + 3) / 4 * count < 512) {
+            const unsigned grid1 = (unsigned)((passes + 3) / 4);
+            if (nt)
+                hipLaunchKernelGGL((k_gemv_popc<MT, G, NCH, 1, true>), dim3(grid1, count), dim3(256), lds, st, b, sh);
+            else
+                hipLaunchKernelGGL((k_gemv_popc<MT, G, NCH, 1, false>), dim3(grid1, count), dim3(256), lds, st, b, sh);
+            return hipGetLastError();
+        }
+    }
     const int64_t waves = (passes + UNR - 1) / UNR;
     const unsigned grid = (unsigned)((waves + 3) / 4);
-    const size_t lds = (size_t)sh.M * 2 * sh.C4 * 16;  // <= 8 * 2 * 128 * 16 = 32 KiB
-    if ((sh.rw & 31) == 0)
+    if (nt)
         hipLaunchKernelGGL((k_gemv_popc<MT, G, NCH, UNR, true>), dim3(grid, count), dim3(256), lds, st, b, sh);
     else
         hipLaunchKernelGGL((k_gemv_popc<MT, G, NCH, UNR, false>), dim3(grid, count), dim3(256), lds, st, b, sh);

@@ -186,7 +186,8 @@ def test_decode_shaped_gemm_matches_oracle(M, N, K):
 
 @pytest.mark.parametrize("rpw,tiles,pf", [(1, 2, 2), (1, 8, 2), (1, 8, 4), (1, 6, 3), (2, 2, 2), (2, 4, 2), (2, 8, 2),
                                           (2, 8, 4), (2, 16, 4), (2, 6, 3), (2, 4, 4), (3, 2, 2), (3, 4, 2), (3, 8, 2),
-                                          (3, 6, 3), (3, 9, 3), (4, 2, 2), (4, 4, 2), (4, 8, 2)])
+                                          (3, 6, 3), (3, 9, 3), (4, 2, 2), (4, 4, 2), (4, 8, 2),
+                                          (1, 1, 1), (2, 1, 1), (2, 3, 1), (3, 1, 1), (4, 1, 1)])
 def test_matrix_core_decode_every_work_split(rpw, tiles, pf):
     """Chunks per wavefront x channel tiles per workgroup x ring depth of the matrix-core decode
     kernel, on shapes with ragged N, a K tail inside a chunk, and more tiles than one workgroup takes."""
