@@ -299,8 +299,8 @@ int bwta_matmul_tt(const uint32_t *maskA, const uint32_t *signA, int64_t strideA
                          {(const uint16_t *)s_a, s_a ? a_scale_mode : BWTA_SCALE_NONE},
                          {(const uint16_t *)s_b, s_b ? b_scale_mode : BWTA_SCALE_NONE},
                          alpha, acc, (uint16_t *)out, ldo, (int64_t)M * N, stride_out};
-    bwta::set_matmul_tt_popc(g_path.load(std::memory_order_relaxed) == BWTA_PATH_POPC);  // comparison path
-    return hip_result(bwta::launch_matmul_tt(g, (hipStream_t)stream));
+    const bool popcount_kernel = g_path.load(std::memory_order_relaxed) == BWTA_PATH_POPC;  // comparison path
+    return hip_result(bwta::launch_matmul_tt(g, popcount_kernel, (hipStream_t)stream));
 }
 
 int bwta_prepare_weights(const void *W, int64_t ldw, int N, int K, uint32_t *wsign, void *s_w,

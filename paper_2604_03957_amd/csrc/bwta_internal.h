@@ -33,8 +33,8 @@ struct MatmulTTArgs {
 };
 
 // launchers (each returns the launch's hipError_t)
-hipError_t launch_matmul_tt(const MatmulTTArgs &g, hipStream_t st);
-void set_matmul_tt_popc(int on);  // 1: the vector-ALU comparison kernel instead of the matrix cores
+// popcount_kernel: the vector-ALU comparison kernel instead of the matrix cores
+hipError_t launch_matmul_tt(const MatmulTTArgs &g, bool popcount_kernel, hipStream_t st);
 hipError_t launch_prepare_weights(const void *W, int64_t ldw, int N, int K, uint32_t *wsign, uint16_t *s_w,
                                   hipStream_t st);
 hipError_t launch_full_mask(uint32_t *mask, int M, int K, hipStream_t st);

@@ -402,13 +402,12 @@ hipError_t launch_fp4_t(const MatmulTTArgs &g, hipStream_t st)
     return hipGetLastError();
 }
 
-int g_matmul_tt_popc = 0;  // comparison path selector
 }  // namespace
 
-hipError_t launch_matmul_tt(const MatmulTTArgs &g, hipStream_t st)
+hipError_t launch_matmul_tt(const MatmulTTArgs &g, bool popcount_kernel, hipStream_t st)
 {
     if (g.M == 0 || g.N == 0 || g.batch == 0) return hipSuccess;
-    if (!g_matmul_tt_popc) {
+    if (!popcount_kernel) {
         if (g.signA && g.signB) return launch_fp4_t<true, true>(g, st);
         if (g.signA) return launch_fp4_t<true, false>(g, st);
         if (g.signB) return launch_fp4_t<false, true>(g, st);
@@ -418,7 +417,5 @@ hipError_t launch_matmul_tt(const MatmulTTArgs &g, hipStream_t st)
     hipLaunchKernelGGL(k_matmul_tt, grid, dim3(256), 0, st, g);
     return hipGetLastError();
 }
-
-void set_matmul_tt_popc(int on) { g_matmul_tt_popc = on; }
 
 }  // namespace bwta
