@@ -4,6 +4,7 @@ force, algebraic invariants and special cases that reduce to textbook routines.
 """
 import itertools
 import math
+import os
 from fractions import Fraction
 
 import numpy as np
@@ -27,10 +28,27 @@ def test_half_decode_matches_ieee_for_every_pattern():
 
 
 def test_paper_hex_constants():
-    # the bitpack constants the kernel section quotes: +0.5, -0.5 and the sign-bit mask
-    assert oracle.half_to_double(0x3800) == 0.5
-    assert oracle.half_to_double(0xB800) == -0.5
-    assert oracle.half_to_double(0x8000) == 0.0 and math.copysign(1, oracle.half_to_double(0x8000)) == -1
+    """The bitpack constants the kernel section prints (tests/golden/bitpack_constants.txt): two
+    binary16 values per 32-bit register; the decoder must read +0.5, -0.5 and a bare sign bit, and
+    the ternary rule must put exactly these thresholds (times the scale) on the +1 / -1 side."""
+    rows = {}
+    for line in open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "bitpack_constants.txt")):
+        if line.strip() and not line.startswith("#"):
+            name, reg, half, value = line.split()[:4]
+            rows[name] = (int(reg, 16), int(half, 16), float(value))
+    assert set(rows) == {"sign_mask", "plus_half", "minus_half"}
+    for reg, half, value in rows.values():
+        assert reg == (half << 16 | half)                       # the same pattern in both halves
+        got = oracle.half_to_double(half)
+        assert got == value and math.copysign(1, got) == math.copysign(1, value)
+    plus, minus = np.array([rows["plus_half"][1]], np.uint16).view(np.float16), np.array([rows["minus_half"][1]], np.uint16).view(np.float16)
+    one = np.array([1.0], np.float16)
+    assert oracle.ternarize(plus.reshape(1, 1), one)[0, 0] == 1     # a / s = +0.5 -> +1 (the printed ">= 0.5")
+    assert oracle.ternarize(minus.reshape(1, 1), one)[0, 0] == 0    # a / s = -0.5 -> 0  (the printed "-0.5 <= a / s")
+    below = np.nextafter(minus, np.float16(-np.inf))
+    assert oracle.ternarize(below.reshape(1, 1), one)[0, 0] == -1
+    w = np.array([[1.0, -1.0, -0.0, 0.0]], np.float16)               # sign bit set -> bit 1, except -0.0 (w >= 0 -> +1)
+    assert list(oracle.sign_weights(w)[0]) == [1, -1, 1, 1]
 
 
 def test_half_encode_round_to_nearest_even():
