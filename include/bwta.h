@@ -147,7 +147,7 @@ int bwta_gemm_prepared(const void *prepared, size_t prepared_bytes, const uint32
  * groups, or a bandwidth measurement over many weight matrices).  `problems` is a HOST array of
  * `count` records of DEVICE pointers with the meaning they have in bwta_gemm; scale modes, ldo
  * and the workspace rule are shared (workspace: count * bwta_workspace_bytes(M, N, K) bytes,
- * 256-byte aligned).  For M <= 64 (decode and small batches) all problems run in one kernel
+ * 256-byte aligned).  For M <= 128 (decode and small batches) all problems run in one kernel
  * launch per 64 problems; otherwise the call is equivalent to `count` bwta_gemm calls.
  */
 typedef struct bwta_gemm_problem {

@@ -172,7 +172,7 @@ DECODE_SHAPES = [(1, 7, 33), (2, 130, 128), (3, 257, 1000), (1, 1001, 4096), (4,
                  (5, 258, 8192), (1, 515, 11008), (4, 130, 11008), (8, 67, 11008), (2, 70, 16384),
                  (3, 40, 16512), (9, 100, 4096), (13, 77, 1408), (16, 257, 11008), (16, 90, 768),
                  (16, 40, 17000), (7, 33, 30000), (12, 16, 512), (15, 17, 513), (17, 100, 4096), (33, 70, 11008),
-                 (64, 130, 1000), (48, 17, 128)]
+                 (64, 130, 1000), (48, 17, 128), (65, 200, 4096), (100, 70, 11008), (128, 129, 1000)]
 
 
 @pytest.mark.parametrize("M,N,K", DECODE_SHAPES)
@@ -209,7 +209,7 @@ def test_decode_seeded_random_shapes():
     both decode kernel families and the dispatcher's choice."""
     rng = np.random.default_rng(20260403)
     for case in range(20):
-        M = int(rng.choice([1, 2, 3, 5, 8, 15, 16, 17, 31, 33, 48, 63, 64]))
+        M = int(rng.choice([1, 2, 3, 5, 8, 15, 16, 17, 31, 33, 48, 63, 64, 65, 96, 127, 128]))
         N = int(rng.integers(1, 700))
         K = int(rng.integers(1, 9000))
         _say("decode random", case, M, N, K)
