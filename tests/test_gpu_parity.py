@@ -220,6 +220,24 @@ def test_decode_seeded_random_shapes():
             assert _check_gemm(t, w, s_a, s_w, B.PATH_POPC)
 
 
+@pytest.mark.parametrize("tile", [0, 22, 23, 21, 12, 11, 222, 2216])
+def test_tiled_matrix_core_kernel_every_tile_variant(tile):
+    """The tiled FP4 kernel's workgroup tiles (128x128 at two and three wavefronts per SIMD, 128x64,
+    64x128, 64x64, split-K, deep ring) and the dispatcher's own choice (0: 64x64 tiles for these few-tile
+    shapes), fp16 output only (the int32 output always takes the 128x128 variant), ragged in M, N and K."""
+    _say("fp4 tile variant", tile)
+    B.set_tile(tile)
+    try:
+        for M, N, K in [(300, 260, 2048), (129, 70, 1100), (200, 513, 4096 + 64)]:
+            t, w, s_a, s_w = _gemm_case(3000 + M, M, N, K)
+            mask, sign, _ = oracle.pack_act(t)
+            want = oracle.epilogue(oracle.gemm_unpacked(t, w), s_a, s_w)
+            _, out = gpu_gemm(mask, sign, oracle.pack_weights(w), s_a, s_w, M, N, K, path=B.PATH_FP4, want_acc=False)
+            assert same_half(out, want)
+    finally:
+        B.set_tile(0)
+
+
 @pytest.mark.parametrize("path", PATHS)
 def test_gemm_config1_tiny(path):
     c = synth.config1()
