@@ -58,6 +58,7 @@ struct DecodeShape {
     int M, N, rw, a_mode, w_mode;  // M tokens in all; grid.z walks them in groups of 16
     int P;  // 16-byte pieces per packed row (rw / 4)
     int T;  // channel tiles per workgroup (a multiple of the ring depth)
+    int G;  // token groups of 16 (ceil(M / 16)); NB = workgroups along the channels per group
     int64_t ldo;
 };
 
@@ -74,10 +75,17 @@ __global__ __launch_bounds__(64 * MAXW, MAXW == 4 && RPW <= 2 ? 5 : 4) void k_ge
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, KW = blockDim.x >> 6;
     const int i = lane & 15, g = lane >> 4;
     const int p = blockIdx.y;
-    const int tok0 = 16 * blockIdx.z;                                 // first token of this group
+    // Workgroups that stream the same weight rows for different token groups sit on the same XCD
+    // (the hardware deals consecutive workgroup ids to the 8 XCDs in turn) and next to each other in
+    // launch order, so the groups after the first find the rows in that XCD's L2:
+    // id = 8 ((tb / 8) G + group) + tb % 8 for tile block tb.
+    const int xq = blockIdx.x >> 3, tgroup = xq % sh.G;
+    const int tblock = (xq / sh.G) * 8 + (blockIdx.x & 7);
+    const int tok0 = 16 * tgroup;                                     // first token of this group
     const int Mg = sh.M - tok0 < 16 ? sh.M - tok0 : 16;               // tokens in it
     const int rw = sh.rw, P = sh.P, T = sh.T;
-    const int64_t tile0 = (int64_t)blockIdx.x * T;
+    const int64_t tile0 = (int64_t)tblock * T;
+    if (16 * tile0 >= sh.N) return;  // the grid is padded to whole rounds of 8 tile blocks
     extern __shared__ __attribute__((aligned(16))) v4u s_lds[];
     v4u *patch = s_lds + w * (16 * PITCH);              // this wavefront's transposition patch
     uint2 *s_part = (uint2 *)(s_lds + KW * (16 * PITCH));  // [T][KW][64 lanes] x four halfs
@@ -316,10 +324,12 @@ hipError_t launch_cfg(const DecodeBatch &b, int count, DecodeShape sh, hipStream
     const int KW = (sh.P + 4 * RPW - 1) / (4 * RPW);
     if (KW < 1 || KW > 16 || sh.T < PF || sh.T % PF != 0 || 16 * sh.T + 16 > 128 * KW) return hipErrorInvalidValue;
     const int tiles = (sh.N + 15) / 16;
-    const dim3 grid((unsigned)((tiles + sh.T - 1) / sh.T), count, (sh.M + 15) / 16), block(64 * KW);
+    sh.G = (sh.M + 15) / 16;
+    const int nb8 = ((tiles + sh.T - 1) / sh.T + 7) / 8 * 8;
+    const dim3 grid((unsigned)(nb8 * sh.G), count, 1), block(64 * KW);
     const size_t lds = decode_lds_bytes(RPW, KW, sh.T);
     if (lds > 64 * 1024) return hipErrorInvalidValue;
-    const bool nt = (sh.rw & 31) == 0;
+    const bool nt = (sh.rw & 31) == 0 && sh.G == 1;  // later token groups are meant to hit the L2
 #define BWTA_DEC_GO(MAXW_)                                                                      \
     do {                                                                                        \
         if (nt) hipLaunchKernelGGL((k_gemv_fp4<RPW, PF, MAXW_, true>), grid, block, lds, st, b, sh);  \
@@ -398,7 +408,7 @@ hipError_t launch_gemv_fp4_grouped(const GemmArgs *gs, int count, hipStream_t st
             b.out[i] = g.out;
         }
         const int P = g0.rw / 4;
-        DecodeShape sh{g0.M, g0.N, g0.rw, g0.s_a.mode, g0.s_w.mode, P, 0, g0.ldo};
+        DecodeShape sh{g0.M, g0.N, g0.rw, g0.s_a.mode, g0.s_w.mode, P, 0, 1, g0.ldo};
         hipError_t e = launch_shape(b, n, sh, st);
         if (e != hipSuccess) return e;
     }
