@@ -38,8 +38,25 @@ def _dev(a, torch):
     return torch.from_numpy(a).to("cuda:0")
 
 
+SETTLE_S = 0.03  # load applied before a timed region; see _settle
+
+
+def _settle(torch, fn, seconds=SETTLE_S):
+    """Untimed load in front of a timed region.  An idle MI355X parks its shader clock near
+    1.2 GHz and takes some milliseconds of work to reach its working frequency (measured: the
+    first 15 ms of a cold loop run about 4 % slow on the FFN step, a 2 ms burst of the
+    7B-shape product 10-15 % slow), so a few warm-up launches after host-side set-up time the
+    ramp, not the kernel."""
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(20):
+            fn()
+        torch.cuda.synchronize()
+
+
 def _event_ms(torch, fn, reps, warmup):
     """Average duration of fn() in ms, HIP events on the current (launch) stream."""
+    _settle(torch, fn)
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
@@ -520,8 +537,10 @@ def run_copy_probe(args, torch, B, synth):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default 2000 for c2_ffn, 200 otherwise)")
+    ap.add_argument("--warmup", type=int, default=None,
+                    help="untimed steps first (default 1000 for c2_ffn, about 30 ms: the clock ramp of an "
+                         "idle GPU; 20 otherwise, where every timed region settles the clock itself)")
     ap.add_argument("--workload", default="c2_ffn", choices=["c2_ffn", "c1_tiny", "c3_prefill", "c4_decode", "c5_block", "attn", "prep", "copy_probe"])
     ap.add_argument("--decode-matrices", type=int, default=64)
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
@@ -529,6 +548,10 @@ def main():
                     help="replay the step from a HIP graph instead of launching eagerly (eager is the default: "
                          "the launch queue stays ahead of the GPU, and a 4-kernel graph replays no faster)")
     args = ap.parse_args()
+    if args.steps is None:
+        args.steps = 2000 if args.workload == "c2_ffn" else 200
+    if args.warmup is None:
+        args.warmup = 1000 if args.workload == "c2_ffn" else 20
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the BWTA hot path is a single-GPU kernel "
               "path that uses no collectives). Re-run with --gpus 1.", file=sys.stderr)
