@@ -355,7 +355,7 @@ int bwta_auto_path(int M, int N, int K)
 {
     (void)N;
     (void)K;
-    // one token: the popcount decode kernel; more: the FP4 matrix cores (decode kernel up to 64
+    // one token: the popcount decode kernel; more: the FP4 matrix cores (decode kernel up to 128
     // tokens, tiled kernel above).  Measured: at two tokens the popcount kernel is level with the
     // matrix cores at K = 4096 and a third slower at K = 11008.
     return M > 1 ? BWTA_PATH_FP4 : BWTA_PATH_POPC;

@@ -55,7 +55,7 @@ struct DecodeBatch {
 };
 
 struct DecodeShape {
-    int M, N, rw, a_mode, w_mode;  // M tokens in all; grid.z walks them in groups of 16
+    int M, N, rw, a_mode, w_mode;  // M tokens in all, worked on in groups of 16
     int P;  // 16-byte pieces per packed row (rw / 4)
     int T;  // channel tiles per workgroup (a multiple of the ring depth)
     int G;  // token groups of 16 (ceil(M / 16)); NB = workgroups along the channels per group
@@ -381,7 +381,7 @@ hipError_t launch_shape(const DecodeBatch &b, int count, DecodeShape sh, hipStre
 
 }  // namespace
 
-// 1..128 tokens (groups of 16 on grid.z, each streaming the weights: the repeats hit the caches;
+// 1..128 tokens (groups of 16 as neighbouring workgroups, each streaming the weights: the repeats hit L2;
 // measured against the tiled kernel at 96 and 128 tokens: 5.9-13.5 us against 13.5-26 us on the 7B shapes);
 // K up to 12 wavefronts x 4 chunks x 512 (their LDS patches and two tiles of partials fill 64 KiB)
 bool gemv_fp4_supported(const GemmArgs &g)
