@@ -142,6 +142,9 @@ class Layer:
         B.bwta_gemm(self.mask, self.sign, self.wsign, self.s_a, self.s_w, None, self.out, self.ws,
                     M=self.M, N=self.N, K=self.K)
 
+    def gemm_prepared_bytes(self):  # second kernel of bwta_linear: E2M1 fragments, weight bits, scales in; fp16 out
+        return self.M * self.K // 2 + self.N * self.rw * 4 + 2 * (self.M + self.N) + 2 * self.M * self.N
+
     def gemm_bytes(self):
         M, N, K = self.M, self.N, self.K
         return N * self.rw * 4 + 2 * M * self.rw * 4 + 2 * (M + N) + 2 * M * N
@@ -218,6 +221,9 @@ def run_c2(args, torch, B, synth):
     roofline = {"bound": "mfma", "kernel": "k_gemm_fp4 (FP4 MFMA product + scale epilogue), mean of the two layers",
                 "achieved": round(achieved, 2), "peak": PEAK_FP4_TOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_FP4_TOPS, 4), "frac_of_int8_peak": round(achieved / PEAK_INT8_TOPS, 4),
+                # the K = 768 -> N = 3072 layer mostly stores: fragments + weight bits + scales in, 25 MB of fp16 out
+                "up_layer_frac_of_hbm_peak": round(layers[0].gemm_prepared_bytes() / (kern[0]["gemm_us"] * 1e-6) / 1e9
+                                                   / PEAK_HBM_GBS, 4),
                 # HBM/fabric bytes per launch (mean of the two layers) from rocprofv3 --pmc FETCH_SIZE and
                 # WRITE_SIZE runs scaled by the copy probe (profiles/traffic_c2_ffn.md): algorithmic bytes
                 # are 20.4e6 (fragments + weight bits + scales in, fp16 out), i.e. nothing is re-read
