@@ -228,7 +228,9 @@ int bwta_auto_path(int M, int N, int K);
  * popcount decode kernel's row split (1000 + 16 * lanes per row + chunks per lane) or the
  * matrix-core decode kernel's work split (2000 + 1024 * ring depth (2..4) + 64 * chunks per
  * wavefront (1..4) + tiles per workgroup (rounded up to a multiple of the ring depth, fewer if LDS
- * does not hold their partials)); 0 restores the built-in choices.  Results do not depend on it. */
+ * does not hold their partials)), or where bwta_linear runs as a single launch (900 never, 901
+ * wherever the one-launch kernel can run, 900 + R the same with R channel splits per token
+ * strip); 0 restores the built-in choices.  Results do not depend on it. */
 int bwta_set_tile(int tile);
 /* Library version, major * 100 + minor. */
 int bwta_version(void);

@@ -152,6 +152,14 @@ int bwta_linear(const void *A, int64_t lda, const void *s_a, int a_scale_mode, c
     if (!aligned(A, 2) || !aligned(wsign, 16)) return BWTA_ERR_ALIGN;
     if (!workspace || workspace_bytes < bwta_workspace_bytes(M, N, K)) return BWTA_ERR_WORKSPACE;
     if (!aligned(workspace, 256)) return BWTA_ERR_ALIGN;
+    if (fp4_uses_fragments(M, K)) {
+        bwta::GemmArgs g{nullptr, nullptr, wsign, M, N, K, (int)bwta_plane_row_words(K),
+                         {(const uint16_t *)s_a, s_a ? a_scale_mode : BWTA_SCALE_NONE},
+                         {(const uint16_t *)s_w, s_w ? w_scale_mode : BWTA_SCALE_NONE},
+                         nullptr, (uint16_t *)out, ldo};
+        if (bwta::linear_fused_supported(A, lda, g))
+            return hip_result(bwta::launch_linear_fused(A, lda, g, (hipStream_t)stream));
+    }
     rc = bwta_prepare_act(A, lda, s_a, a_scale_mode, M, K, workspace, workspace_bytes, stream);
     if (rc != BWTA_OK) return rc;
     return bwta_gemm_prepared(workspace, workspace_bytes, wsign, M, N, K, s_a, a_scale_mode, s_w, w_scale_mode,
@@ -376,6 +384,11 @@ int bwta_set_tile(int tile)
         return BWTA_OK;
     }
     bwta::set_gemv_tile(0, 0);
+    if (tile >= 900 && tile < 1000) {  // one-launch linear: 900 never, 901 wherever it can run, 900 + R the same with R channel splits
+        bwta::set_linear_fused(tile > 900 ? 2 : 0, tile > 901 ? tile - 900 : 0);
+        return BWTA_OK;
+    }
+    bwta::set_linear_fused(1, 0);
     bwta::set_fp4_tile(tile);
     return BWTA_OK;
 }

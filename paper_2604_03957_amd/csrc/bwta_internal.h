@@ -58,6 +58,10 @@ hipError_t launch_gemm_mfma(const GemmArgs &g, hipStream_t st);
 
 size_t gemm_fp4_frag_bytes(int M, int K);
 void set_fp4_tile(int t);
+// the whole linear in one launch (short K, fp16 in, fp16 out)
+bool linear_fused_supported(const void *A, int64_t lda, const GemmArgs &g);
+hipError_t launch_linear_fused(const void *A, int64_t lda, const GemmArgs &g, hipStream_t st);
+void set_linear_fused(int mode, int r);
 void set_gemv_tile(int g, int nch);
 hipError_t launch_gemm_fp4(const GemmArgs &g, uint32_t *frag, bool frag_ready, hipStream_t st);
 hipError_t launch_quantize_to_fp4(const void *A, int64_t lda, ScaleArg s_a, int M, int K, uint32_t *frag,

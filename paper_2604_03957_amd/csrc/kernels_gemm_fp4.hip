@@ -78,6 +78,32 @@ __global__ __launch_bounds__(256) void k_planes_to_fp4(const uint32_t *__restric
     }
 }
 
+// 8 fp16 values of one row (lane j of a quad holds elements 8 j .. 8 j + 7 of a 32-element word) ->
+// the dword this lane contributes to the word's fragment: nibble i of dword d holds element
+// 4 i + d (bit 1 = non-zero, bit 3 = negative).  Compares are exact in fp32; NaN thresholds (invalid
+// scale) and NaN values fail both.
+__device__ __forceinline__ uint32_t fragment_dword(const uint4 &x, float hthr, float nthr, int j)
+{
+    const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+    uint32_t V = 0;  // byte d = nibbles of elements d (low) and d + 4 (high): mask -> bit 1, sign -> bit 3
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float a = half_bits_to_float((uint16_t)(w[e >> 1] >> (16 * (e & 1))));
+        uint32_t sel = a >= hthr ? 1u : 0u;  // mask bit; NaN fails both compares
+        sel = a < nthr ? 5u : sel;           // mask bit and, two places up, the sign bit
+        const int base = 8 * (e & 3) + 4 * (e >> 2);
+        V = (sel << (base + 1)) | V;
+    }
+    // quad byte transpose: lane d of the quad collects byte d of every lane -> dword d of the word
+    const uint32_t x0 = __builtin_amdgcn_mov_dpp(V, 0x00, 0xf, 0xf, true);  // quad_perm [0,0,0,0]
+    const uint32_t x1 = __builtin_amdgcn_mov_dpp(V, 0x55, 0xf, 0xf, true);  // [1,1,1,1]
+    const uint32_t x2 = __builtin_amdgcn_mov_dpp(V, 0xaa, 0xf, 0xf, true);  // [2,2,2,2]
+    const uint32_t x3 = __builtin_amdgcn_mov_dpp(V, 0xff, 0xf, 0xf, true);  // [3,3,3,3]
+    const uint32_t sh = 8 * j;
+    return ((x0 >> sh) & 0xffu) | (((x1 >> sh) & 0xffu) << 8) | (((x2 >> sh) & 0xffu) << 16) |
+                       (((x3 >> sh) & 0xffu) << 24);
+}
+
 // fp16 activations -> E2M1 fragments in one pass (ternarise by the paper's threshold rule and
 // emit the GEMM operand directly; no bit planes in between).  A lane takes 8 consecutive
 // elements (one 128-bit load); the 4 lanes of a quad cover one 32-element word, whose 4 nibble
@@ -147,24 +173,7 @@ __global__ __launch_bounds__(256) void k_quantize_to_fp4(const uint16_t *__restr
 #pragma unroll
     for (int it = 0; it < QF_R; ++it) {
         const int q = q0 + 2 * it;
-        const uint32_t w[4] = {x[it].x, x[it].y, x[it].z, x[it].w};
-        uint32_t V = 0;  // byte d = nibbles of elements d (low) and d + 4 (high): mask -> bit 1, sign -> bit 3
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float a = half_bits_to_float((uint16_t)(w[e >> 1] >> (16 * (e & 1))));
-            uint32_t sel = a >= hthr ? 1u : 0u;  // mask bit; NaN fails both compares
-            sel = a < nthr ? 5u : sel;           // mask bit and, two places up, the sign bit
-            const int base = 8 * (e & 3) + 4 * (e >> 2);
-            V = (sel << (base + 1)) | V;
-        }
-        // quad byte transpose: lane d of the quad collects byte d of every lane -> dword d of the word
-        const uint32_t x0 = __builtin_amdgcn_mov_dpp(V, 0x00, 0xf, 0xf, true);  // quad_perm [0,0,0,0]
-        const uint32_t x1 = __builtin_amdgcn_mov_dpp(V, 0x55, 0xf, 0xf, true);  // [1,1,1,1]
-        const uint32_t x2 = __builtin_amdgcn_mov_dpp(V, 0xaa, 0xf, 0xf, true);  // [2,2,2,2]
-        const uint32_t x3 = __builtin_amdgcn_mov_dpp(V, 0xff, 0xf, 0xf, true);  // [3,3,3,3]
-        const uint32_t sh = 8 * j;
-        const uint32_t D = ((x0 >> sh) & 0xffu) | (((x1 >> sh) & 0xffu) << 8) | (((x2 >> sh) & 0xffu) << 16) |
-                           (((x3 >> sh) & 0xffu) << 24);
+        const uint32_t D = fragment_dword(x[it], hthr, nthr, j);
         int step, half;
         word_slot(q, step, half);
         if (step < s_pad) frag[(((int64_t)rb * s_pad + step) * 64 + half * 32 + row) * 4 + j] = D;
@@ -183,6 +192,75 @@ __device__ __forceinline__ v8i widen_w(uint32_t x, uint32_t m88, uint32_t c22)
     r[3] = (int)((x & m88) | c22);
     r[4] = r[5] = r[6] = r[7] = 0;
     return r;
+}
+
+// Workgroup ids are dealt round-robin to the 8 XCDs; give every XCD a contiguous range of tile
+// numbers, and number the tiles in groups of 4 token strips (strip fastest) so that the tiles an
+// XCD works on at one time share both their activation strips and their weight tile in its L2.
+__device__ __forceinline__ void tile_of_workgroup(int tiles_n, int tiles_total, int &tm, int &tn)
+{
+    const int L = blockIdx.x, xcd = L & 7, k = L >> 3;
+    const int chunk = tiles_total >> 3, rem = tiles_total & 7;
+    const int id = xcd * chunk + (xcd < rem ? xcd : rem) + k;
+    const int tiles_m = tiles_total / tiles_n;
+    const int per_group = 4 * tiles_n;
+    const int grp = id / per_group, in_grp = id - grp * per_group;
+    const int first_m = 4 * grp;
+    const int gsz = tiles_m - first_m < 4 ? tiles_m - first_m : 4;
+    tm = first_m + in_grp % gsz;
+    tn = in_grp / gsz;
+}
+
+// fp16 epilogue of one wavefront: WM x WN accumulator blocks -> scaled, exactly rounded halves,
+// regrouped through the wavefront's LDS strip into 16-byte row-contiguous stores.  Lane (r32, h)
+// of block (j, i) holds token 32 i + r32 and channels 32 j + 8 g + 4 h + q (register 4 g + q).
+// sa_w / sw_w: this wavefront's token and channel scales in LDS.
+template <int WM, int WN>
+__device__ __forceinline__ void store_tile_fp16(const v16f (&acc)[WN][WM], const GemmArgs &g, const float *sa_w,
+                                                const float *sw_w, uint16_t *strip, int m_wave, int n_wave, int lane)
+{
+    const int r32 = lane & 31, h = lane >> 5;
+    constexpr int PITCH = 32 * WN + 8;  // halfs; 16-byte aligned rows, conflict-free 8-byte writes
+    const bool full = (m_wave + 32 * WM <= g.M) && (n_wave + 32 * WN <= g.N) && ((g.ldo & 7) == 0) &&
+                      (((uintptr_t)g.out & 15) == 0);
+    constexpr int LPR = 4 * WN, RPI = 64 / LPR;  // lanes per token row (8 halfs each), rows per store
+#pragma unroll
+    for (int i = 0; i < WM; ++i) {
+        const float sa = sa_w[32 * i + r32];
+#pragma unroll
+        for (int j = 0; j < WN; ++j) {
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const int nl = 32 * j + 8 * gq + 4 * h;
+                const float4 sw = *(const float4 *)(sw_w + nl);
+                uint2 hv;  // four consecutive channels of this token, exactly rounded
+                hv.x = scaled_to_half2(acc[j][i][4 * gq], sa * sw.x, acc[j][i][4 * gq + 1], sa * sw.y);
+                hv.y = scaled_to_half2(acc[j][i][4 * gq + 2], sa * sw.z, acc[j][i][4 * gq + 3], sa * sw.w);
+                *(uint2 *)(strip + r32 * PITCH + nl) = hv;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+        for (int rr = 0; rr < 32; rr += RPI) {
+            const int row = rr + lane / LPR, c8 = 8 * (lane % LPR);
+            const int mo = m_wave + 32 * i + row, n = n_wave + c8;
+            const uint4 q = *(const uint4 *)(strip + row * PITCH + c8);
+            uint16_t *dst = g.out + (int64_t)mo * g.ldo + n;
+            if (full) {
+                typedef unsigned v4u __attribute__((ext_vector_type(4)));
+                const v4u qv = {q.x, q.y, q.z, q.w};
+                __builtin_nontemporal_store(qv, (v4u *)dst);  // streamed once, never re-read here
+            } else if (mo < g.M && n < g.N) {
+                const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (n + e < g.N) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    }
 }
 
 constexpr int WD_PITCH = 20;  // dwords per LDS weight row: 16 words (512 k) + 4 pad
@@ -218,23 +296,8 @@ void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, int ti
     static_assert(D == 8 || D == 16, "activation prefetch distance in k steps: one or two slabs");
     extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
 
-    // Workgroup ids are dealt round-robin to the 8 XCDs; give every XCD a contiguous range of
-    // tile numbers, and number the tiles in groups of 4 token strips (strip fastest) so that the
-    // tiles an XCD works on at one time share both their activation strips and their weight
-    // tile in its L2.
     int tm, tn;
-    {
-        const int L = blockIdx.x, xcd = L & 7, k = L >> 3;
-        const int chunk = tiles_total >> 3, rem = tiles_total & 7;
-        const int id = xcd * chunk + (xcd < rem ? xcd : rem) + k;
-        const int tiles_m = tiles_total / tiles_n;
-        const int per_group = 4 * tiles_n;
-        const int grp = id / per_group, in_grp = id - grp * per_group;
-        const int first_m = 4 * grp;
-        const int gsz = tiles_m - first_m < 4 ? tiles_m - first_m : 4;
-        tm = first_m + in_grp % gsz;
-        tn = in_grp / gsz;
-    }
+    tile_of_workgroup(tiles_n, tiles_total, tm, tn);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int kg = KS == 1 ? 0 : wave / C::GROUP_WAVES;  // k group
@@ -446,48 +509,8 @@ void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, int ti
     const float *sw_lds = sc_lds, *sa_lds = sc_lds + C::BN;
     // the loop's last barrier retired every read of the weight slabs, whose LDS the strips reuse
     uint16_t *strip = (uint16_t *)(smem + C::BN) + wl * C::STRIP_HALFS;
-    constexpr int PITCH = 32 * WN + 8;  // halfs; 16-byte aligned rows, conflict-free 8-byte writes
     if (kg != 0) return;  // no barrier below this point
-    const bool full = (m_wave + 32 * WM <= g.M) && (n_wave + 32 * WN <= g.N) && ((g.ldo & 7) == 0) &&
-                      (((uintptr_t)g.out & 15) == 0);
-    constexpr int LPR = 4 * WN, RPI = 64 / LPR;  // lanes per token row (8 halfs each), rows per store
-#pragma unroll
-    for (int i = 0; i < WM; ++i) {
-        const float sa = sa_lds[wm * WM * 32 + 32 * i + r32];
-#pragma unroll
-        for (int j = 0; j < WN; ++j) {
-#pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                const int nl = 32 * j + 8 * gq + 4 * h;
-                const float4 sw = *(const float4 *)(sw_lds + wn * WN * 32 + nl);
-                uint2 hv;  // four consecutive channels of this token, exactly rounded
-                hv.x = scaled_to_half2(acc[j][i][4 * gq], sa * sw.x, acc[j][i][4 * gq + 1], sa * sw.y);
-                hv.y = scaled_to_half2(acc[j][i][4 * gq + 2], sa * sw.z, acc[j][i][4 * gq + 3], sa * sw.w);
-                *(uint2 *)(strip + r32 * PITCH + nl) = hv;
-            }
-        }
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-#pragma unroll
-        for (int rr = 0; rr < 32; rr += RPI) {
-            const int row = rr + lane / LPR, c8 = 8 * (lane % LPR);
-            const int mo = m_wave + 32 * i + row, n = n_wave + c8;
-            const uint4 q = *(const uint4 *)(strip + row * PITCH + c8);
-            uint16_t *dst = g.out + (int64_t)mo * g.ldo + n;
-            if (full) {
-                typedef unsigned v4u __attribute__((ext_vector_type(4)));
-                const v4u qv = {q.x, q.y, q.z, q.w};
-                __builtin_nontemporal_store(qv, (v4u *)dst);  // streamed once, never re-read here
-            } else if (mo < g.M && n < g.N) {
-                const uint32_t w[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if (n + e < g.N) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
-            }
-        }
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    }
+    store_tile_fp16<WM, WN>(acc, g, sa_lds + wm * WM * 32, sw_lds + wn * WN * 32, strip, m_wave, n_wave, lane);
 }
 
 template <int WM, int WN, int WAVES_M, int WAVES_N, int OCC, bool WITH_ACC, int KS = 1, int D = 8>
@@ -508,6 +531,150 @@ hipError_t launch(const GemmArgs &g, const uint32_t *frag, int s_pad, hipStream_
                        C::SMEM_BYTES, st, g, frag, s_pad, tiles_n, (int)total);
     return hipGetLastError();
 }
+
+// ---------------------------------------------------------------------------------------------
+// bwta_linear in one launch for short K (K <= 1024): ternarise + product + epilogue.  With fp16
+// activations in and few k steps per output, the two-kernel form spends most of its time on what a
+// launch costs however little it computes (ramp, one memory round trip before the first
+// instruction that needs data, drain) and on writing and re-reading the fragments.
+// A workgroup owns one strip of 32 tokens and 1/R of the channels.  It ternarises its strip straight
+// into LDS in MFMA operand order (all of K: at most 16 KiB), so the activation operand of every
+// MFMA comes from LDS and is shared by all channels; the R workgroups of a strip repeat that part.
+// Each wavefront then walks its channel blocks four at a time: the weight bits of a group are
+// loaded from global memory directly in operand layout (lane (r, h) takes four words of row r; the
+// fragments are produced here, so words are dealt to k steps in the order that makes those four
+// words adjacent), all of K at once, and requested a group ahead, so the K loop runs out of
+// registers and LDS and the wavefronts share no barrier after the first: their epilogues and
+// stores overlap the others' MFMAs.
+constexpr int FL_STRIP_HALFS = 32 * (32 * 4 + 8);  // room for the widest group
+
+// word j of a 256-k chunk feeds k step j % 4 of the chunk on lane half j / 4
+template <int NCH, int FL_CB>  // 256-k chunks of K (1..4); channel blocks (of 32) per group: 1, 2 or 4
+__global__ __launch_bounds__(256) void k_linear_fused(const uint16_t *__restrict__ A, int64_t lda, GemmArgs g, int R,
+                                                      int cbw /* channel blocks per workgroup, a multiple of 4 FL_CB */)
+{
+    extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
+    constexpr int NSTEP = 4 * NCH;
+    uint32_t *sA = smem;                                   // [NSTEP][64 lanes][4 dwords]
+    float *s_sa = (float *)(smem + NSTEP * 256);           // [32] token scales
+    float *s_sw = s_sa + 32;                               // [32 cbw] channel scales
+    uint16_t *strips = (uint16_t *)(s_sw + 32 * cbw);      // [4 wavefronts][FL_STRIP_HALFS]
+
+    // the R workgroups of a strip sit 8 ids apart: same XCD, so the strip's second reader hits its L2
+    const int nstrips = (g.M + 31) >> 5;
+    const int id = blockIdx.x, kq = id >> 3;
+    const int split = kq % R, strip_id = (kq / R) * 8 + (id & 7);
+    if (strip_id >= nstrips) return;  // the grid is padded to rounds of 8 strips
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int rw = g.rw;
+    const int m0 = 32 * strip_id;
+    const int cb0 = split * cbw;               // first channel block of this workgroup
+    const int ncb = (g.N + 31) >> 5;           // channel blocks in all
+    const int per_wave = cbw >> 2;             // channel blocks per wavefront, a multiple of FL_CB
+    const int wcb0 = cb0 + wave * per_wave;    // first channel block of this wavefront
+
+    // ---- requests, smallest first: scales, the strip's activations, the first group's weight bits
+    const int quad = tid >> 2, j = tid & 3;
+    const int row = quad & 31, m = m0 + row;
+    const int mc = m < g.M ? m : 0;
+    const bool have_sa = g.s_a.mode != 0 && g.s_a.ptr != nullptr;
+    const uint16_t sa_bits = *(have_sa ? g.s_a.ptr + (g.s_a.mode == 1 ? 0 : mc) : A);
+    const bool have_sw = g.s_w.mode != 0 && g.s_w.ptr != nullptr;
+    constexpr int SW_PER = 8;  // 8 x 256 channel scales at most (cbw <= 64)
+    uint16_t sw_bits[SW_PER];
+#pragma unroll
+    for (int i = 0; i < SW_PER; ++i) {
+        const int n = 32 * cb0 + tid + 256 * i;
+        const bool want = tid + 256 * i < 32 * cbw && n < g.N && have_sw;
+        sw_bits[i] = *(want ? g.s_w.ptr + (g.s_w.mode == 1 ? 0 : n) : A);
+    }
+    uint4 x[NSTEP];
+#pragma unroll
+    for (int it = 0; it < NSTEP; ++it) {
+        const int q = 2 * it + (quad >> 5), k0 = 32 * q + 8 * j;
+        const bool inb = m < g.M && k0 < g.K;  // lanes outside re-read the first bytes and drop them
+        x[it] = *(const uint4 *)(A + (inb ? (int64_t)m * lda + k0 : 0));
+    }
+    const int r32 = lane & 31, h = lane >> 5;
+    uint4 wq[NCH][FL_CB];
+    auto fetch_w = [&](int cb_first) {
+#pragma unroll
+        for (int c = 0; c < FL_CB; ++c) {
+            int n = 32 * (cb_first + c) + r32;
+            n = n < g.N ? n : g.N - 1;  // rows past the end are never stored
+            const uint32_t *wrow = g.wsign + (int64_t)n * rw;
+#pragma unroll
+            for (int ch = 0; ch < NCH; ++ch) {
+                int kw = 8 * ch + 4 * h;
+                kw = kw < rw ? kw : rw - 4;  // words past the end meet zero activations
+                wq[ch][c] = *(const uint4 *)(wrow + kw);
+            }
+        }
+    };
+    fetch_w(wcb0);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- ternarise the strip into LDS
+    float hthr = __builtin_nanf("");
+    {
+        const float sc = have_sa ? half_bits_to_float(sa_bits) : 1.0f;
+        if (m < g.M && (sc > 0.0f) && (sc < __builtin_inff())) hthr = 0.5f * sc;
+        if ((quad >> 5) == 0 && j == 0) s_sa[row] = m < g.M ? sc : 0.0f;
+    }
+    const float nthr = -hthr;
+#pragma unroll
+    for (int i = 0; i < SW_PER; ++i) {
+        const int e = tid + 256 * i, n = 32 * cb0 + e;
+        if (e < 32 * cbw) s_sw[e] = n < g.N ? (have_sw ? half_bits_to_float(sw_bits[i]) : 1.0f) : 0.0f;
+    }
+#pragma unroll
+    for (int it = 0; it < NSTEP; ++it) {
+        const int q = 2 * it + (quad >> 5), k0 = 32 * q + 8 * j;
+        uint4 v = x[it];
+        if (!(m < g.M && k0 < g.K)) v = make_uint4(0, 0, 0, 0);
+        const uint32_t D = fragment_dword(v, hthr, nthr, j);
+        const int jw = q & 7, step = 4 * (q >> 3) + (jw & 3), half = jw >> 2;
+        sA[(step * 64 + half * 32 + row) * 4 + j] = D;
+    }
+    __syncthreads();
+
+    // ---- products: no barrier from here on
+    uint32_t m88 = 0x88888888u, c22 = 0x22222222u;
+    asm volatile("" : "+s"(m88));
+    asm volatile("" : "+v"(c22));
+    uint16_t *strip = strips + wave * FL_STRIP_HALFS;
+    const uint4 *sAl = (const uint4 *)sA + lane;
+    for (int grp = 0; grp * FL_CB < per_wave; ++grp) {
+        const int gcb = wcb0 + grp * FL_CB;
+        if (gcb >= ncb) break;
+        v16f acc[FL_CB][1];
+#pragma unroll
+        for (int c = 0; c < FL_CB; ++c)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[c][0][v] = 0.0f;
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch)
+#pragma unroll
+            for (int st = 0; st < 4; ++st) {
+                const uint4 av = sAl[(4 * ch + st) * 64];
+                v8i a;
+                a[0] = (int)av.x; a[1] = (int)av.y; a[2] = (int)av.z; a[3] = (int)av.w;
+                a[4] = a[5] = a[6] = a[7] = 0;
+#pragma unroll
+                for (int c = 0; c < FL_CB; ++c) {
+                    const uint4 w4 = wq[ch][c];
+                    const v8i b = widen_w(st == 0 ? w4.x : st == 1 ? w4.y : st == 2 ? w4.z : w4.w, m88, c22);
+                    acc[c][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b, a, acc[c][0], 4, 4, 0, 0, 0, 0);
+                }
+            }
+        // the next group's bits are requested before this group's results are scaled and stored
+        if ((grp + 1) * FL_CB < per_wave) fetch_w(gcb + FL_CB < ncb ? gcb + FL_CB : gcb);
+        store_tile_fp16<1, FL_CB>(acc, g, s_sa, s_sw + 32 * (gcb - cb0), strip, m0, 32 * gcb, lane);
+    }
+}
+
+static int g_linear_fused = 1;  // 0: never; 1: where it pays; 2: wherever it can run; g_linear_fused_r > 0 forces the channel splits
+static int g_linear_fused_r = 0;
 
 }  // namespace
 
@@ -538,6 +705,52 @@ hipError_t launch_quantize_to_fp4(const void *A, int64_t lda, ScaleArg s_a, int 
         hipLaunchKernelGGL(k_quantize_to_fp4<1>, dim3(s_pad, rb_pad), dim3(256), 0, st, (const uint16_t *)A, lda, s_a, M,
                            K, s_pad, frag, vec_ok);
     return hipGetLastError();
+}
+
+// One launch for the whole linear when K is short (see k_linear_fused).  The workgroups of a strip
+// each ternarise it again and a weight operand feeds a single MFMA, so the kernel's cost grows
+// about three times as fast with K as the two-kernel form's, while its fixed cost is 2 us lower;
+// measured at M = 4096 it wins up to K = 256 at N = 3072 (8.4 against 10.4 us) and up to K = 768 at
+// N = 768 (8.0 against 9.7 us), and is level or behind beyond.
+bool linear_fused_supported(const void *A, int64_t lda, const GemmArgs &g)
+{
+    if (g_linear_fused == 0) return false;
+    const bool pays = g.K <= 256 || (g.K <= 768 && g.N <= 1024);
+    return (pays || g_linear_fused == 2) && g.K <= 1024 && g.M >= 256 && g.N >= 128 && g.out != nullptr &&
+           g.acc == nullptr && ((uintptr_t)A % 16) == 0 && (lda % 8) == 0 && (g.K % 8) == 0;
+}
+
+hipError_t launch_linear_fused(const void *A, int64_t lda, const GemmArgs &g, hipStream_t st)
+{
+    const int nstrips = (g.M + 31) / 32, ncb = (g.N + 31) / 32;
+    // channel splits (measured at M = 4096): about 1024 workgroups while K <= 256, where the repeated
+    // ternarisation is cheap, about 256 beyond; at most 64 channel blocks per workgroup
+    const int want_wgs = g.K <= 256 ? 1024 : 256;
+    int R = g_linear_fused_r > 0 ? g_linear_fused_r : (want_wgs + nstrips - 1) / nstrips;
+    if (R < (ncb + 63) / 64) R = (ncb + 63) / 64;
+    const int pw = ((ncb + R - 1) / R + 3) / 4;  // channel blocks per wavefront
+    const int CB = pw >= 4 ? 4 : pw >= 2 ? 2 : 1;
+    const int cbw = 4 * ((pw + CB - 1) / CB * CB);
+    if (cbw > 64) return hipErrorInvalidValue;
+    R = (ncb + cbw - 1) / cbw;
+    const int nch = (g.rw + 7) / 8;
+    const size_t smem = (size_t)nch * 4 * 1024 + (32 + 32 * cbw) * 4 + 4 * FL_STRIP_HALFS * 2;
+    const dim3 grid((unsigned)((nstrips + 7) / 8 * 8 * R)), block(256);
+#define BWTA_FL(N_, C_)                                                                                          \
+    if (nch == N_ && CB == C_) {                                                                                 \
+        hipLaunchKernelGGL((k_linear_fused<N_, C_>), grid, block, smem, st, (const uint16_t *)A, lda, g, R, cbw); \
+        return hipGetLastError();                                                                                \
+    }
+    BWTA_FL(1, 1) BWTA_FL(1, 2) BWTA_FL(1, 4) BWTA_FL(2, 1) BWTA_FL(2, 2) BWTA_FL(2, 4)
+    BWTA_FL(3, 1) BWTA_FL(3, 2) BWTA_FL(3, 4) BWTA_FL(4, 1) BWTA_FL(4, 2) BWTA_FL(4, 4)
+#undef BWTA_FL
+    return hipErrorInvalidValue;
+}
+
+void set_linear_fused(int mode, int r)
+{
+    g_linear_fused = mode;
+    g_linear_fused_r = r;
 }
 
 static int g_fp4_tile = 0;

@@ -324,6 +324,27 @@ def test_linear_ragged_shapes_and_special_values(M, N, K, path):
     assert same_half(out, want)
 
 
+@pytest.mark.parametrize("hook", [0, 901, 902, 903, 906, 912])
+@pytest.mark.parametrize("M,N,K", [(256, 128, 128), (300, 260, 768), (1000, 3072, 768), (289, 1000, 1000), (700, 513, 1024), (257, 130, 136)])
+def test_linear_one_launch_short_k(M, N, K, hook):
+    """bwta_linear as a single kernel (K <= 1024): every chunk count, channel splits forced to
+    1, 2, 3, 6 and 12 as well as the launcher's own choice (which makes every group width appear; 0 = the
+    dispatcher decides whether to use the kernel at all),
+    ragged M and N, special values, an invalid token scale."""
+    _say("one-launch linear", M, N, K, "hook", hook)
+    A, s = _activation_case(500 + M, M, K)
+    s[5] = np.float16(0.0)
+    w = synth.binary_pm1(33, M + N, (N, K))
+    s_w = synth.scales(33, 7, N)
+    _, _, want = oracle.linear(A, s, w, s_w)
+    B.set_tile(hook)
+    try:
+        out = gpu_linear(A, s, gpu_pack_weights(w), s_w, N, path=B.PATH_FP4)
+    finally:
+        B.set_tile(0)
+    assert same_half(out, want)
+
+
 def test_linear_strided_input_and_output():
     M, N, K, lda, ldo = 50, 72, 520, 528, 80
     A, s = _activation_case(9, M, lda)
