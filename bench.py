@@ -403,9 +403,10 @@ def run_c1(args, torch, B, synth):
 
 class Block:
     """One 7B-style decoder block: the seven linears are BWTA layers (ternarise on the fly, one
-    ternarisation shared by Q/K/V and by gate/up; the per-token activation scale is the library's
-    bwta_act_scale, the value training starts the scale from); norms, attention and SiLU are plain
-    torch fp16 ops (the paper keeps nonlinearities in high precision)."""
+    ternarisation shared by Q/K/V and by gate/up; the per-token activation scale, the value
+    training starts the scale from, is computed in the same pass: bwta_prepare_act_autoscale);
+    norms, attention and SiLU are plain torch fp16 ops (the paper keeps nonlinearities in high
+    precision)."""
 
     def __init__(self, cfg, torch, B):
         self.torch, self.B = torch, B
@@ -437,46 +438,44 @@ class Block:
         self.B.bwta_act_scale(a, s, M=a.shape[0], K=a.shape[1])
         return s
 
+    def _prep(self, a, prep, K):  # token scales and the ternarised operand in one pass over the activations
+        s = self.torch.empty((a.shape[0],), dtype=self.torch.float16, device=a.device)
+        self.B.bwta_prepare_act_autoscale(a, s, prep, M=a.shape[0], K=K)
+        return s
+
     def _lin(self, prep, s_a, nm, out, K, N):
         self.B.bwta_gemm_prepared(prep, self.w[nm], s_a, self.sw[nm], None, out, M=self.S, N=N, K=K)
 
     def forward(self, bwta_only=False):
         """bwta_only: run just the 4 ternarisations and 7 products on whatever the buffers hold."""
         torch, B, S, H, F = self.torch, self.B, self.S, self.H, self.F
-        h = self.x if bwta_only else self._norm(self.x)
-        s = self.s1 if bwta_only else self._scale(h)
-        B.bwta_prepare_act(h, s, self.prep_h, M=S, K=H)
+        h = self.h if bwta_only else self._norm(self.x)
+        s = self._prep(h, self.prep_h, H)
         for nm, out in (("wq", self.q), ("wk", self.k), ("wv", self.v)):
             self._lin(self.prep_h, s, nm, out, H, H)
         if bwta_only:
-            att, s2 = self.att, self.s2
+            att = self.att
         else:
             hd = H // self.heads
             q, k, v = (t.view(S, self.heads, hd).transpose(0, 1).unsqueeze(0) for t in (self.q, self.k, self.v))
             att = torch.nn.functional.scaled_dot_product_attention(q, k, v, is_causal=True)
             att = att.squeeze(0).transpose(0, 1).reshape(S, H).contiguous()
-            s2 = self._scale(att)
-        B.bwta_prepare_act(att, s2, self.prep_h, M=S, K=H)
+        s2 = self._prep(att, self.prep_h, H)
         self._lin(self.prep_h, s2, "wo", self.o, H, H)
         if bwta_only:
-            h2, s3 = self.h2, self.s3
+            h2 = self.h2
         else:
             x1 = self.x + self.o
             h2 = self._norm(x1)
-            s3 = self._scale(h2)
-        B.bwta_prepare_act(h2, s3, self.prep_h, M=S, K=H)
+        s3 = self._prep(h2, self.prep_h, H)
         self._lin(self.prep_h, s3, "wgate", self.g, H, F)
         self._lin(self.prep_h, s3, "wup", self.u, H, F)
-        if bwta_only:
-            act, s4 = self.act, self.s4
-        else:
-            act = torch.nn.functional.silu(self.g) * self.u
-            s4 = self._scale(act)
-        B.bwta_prepare_act(act, s4, self.prep_f, M=S, K=F)
+        act = self.act if bwta_only else torch.nn.functional.silu(self.g) * self.u
+        s4 = self._prep(act, self.prep_f, F)
         self._lin(self.prep_f, s4, "wdown", self.d, F, H)
         if bwta_only:
             return None
-        self.s1, self.att, self.s2, self.h2, self.s3, self.act, self.s4 = s, att, s2, h2, s3, act, s4
+        self.h, self.att, self.h2, self.act = h, att, h2, act
         return x1 + self.d
 
 
@@ -497,8 +496,8 @@ def run_c5(args, torch, B, synth):
             "config": {"workload": "c5_block: hidden 4096, FFN 11008, 32 heads, seq 2048, batch 1; Laplace(0,1) input"},
             "kernels": {"bwta_part_us": round(ms_bwta * 1e3, 1), "bwta_share": round(ms_bwta / ms_block, 3),
                         "bwta_effective_TOPS": round(ops / (ms_bwta * 1e-3) / 1e12, 1),
-                        "note": "bwta part = 4 ternarisations + 7 products; the rest is torch fp16 attention, "
-                                "RMSNorm, SiLU, residuals and the four per-token scale kernels (bwta_act_scale)"}}
+                        "note": "bwta part = 4 ternarisations (each computing its per-token scales in the same "
+                                "pass) + 7 products; the rest is torch fp16 attention, RMSNorm, SiLU and residuals"}}
 
 
 def run_prep(args, torch, B, synth):
@@ -514,16 +513,22 @@ def run_prep(args, torch, B, synth):
     steps = max(5, args.steps // 10)
     tw = _event_ms(torch, lambda: B.bwta_prepare_weights(W, wsign, s_w, N=N, K=K), steps, 2)
     ta = _event_ms(torch, lambda: B.bwta_act_scale(A, s_a, M=M, K=K), steps, 2)
+    prep = torch.empty(B.prepared_bytes(M, K), dtype=torch.uint8, device=dev)
+    tp = _event_ms(torch, lambda: B.bwta_prepare_act(A, s_a, prep, M=M, K=K), steps, 2)
+    tf = _event_ms(torch, lambda: B.bwta_prepare_act_autoscale(A, s_a, prep, M=M, K=K), steps, 2)
     bw = (2.0 * N * K + N * K / 8 + 2 * N) / (tw * 1e-3) / 1e9
     ba = (2.0 * M * K + 2 * M) / (ta * 1e-3) / 1e9
     return {"metric": "BWTA weight preparation achieved HBM GB/s", "value": round(bw, 1), "unit": "GB/s", "n_gpus": 1,
             "steps": steps, "warmup": 2, "ms_per_step": round(tw, 5), "higher_is_better": True, "scaling": "weak",
             "vs_baseline": None, "dtype": "int64 (exact row sums of fp16 values)", "data": "synthetic",
-            "config": {"workload": "prep: bwta_prepare_weights on fp16 [4096,11008], bwta_act_scale on fp16 [2048,11008]"},
+            "config": {"workload": "prep: bwta_prepare_weights on fp16 [4096,11008]; bwta_act_scale, bwta_prepare_act and "
+                                   "bwta_prepare_act_autoscale on fp16 [2048,11008]"},
             "roofline": {"bound": "hbm", "kernel": "k_prepare_weights", "achieved": round(bw, 1), "peak": PEAK_HBM_GBS,
                          "unit": "GB/s", "frac": round(bw / PEAK_HBM_GBS, 4), "traffic": None},
             "kernels": {"prepare_weights_us": round(tw * 1e3, 1), "prepare_weights_GBs": round(bw, 1),
-                        "act_scale_us": round(ta * 1e3, 1), "act_scale_GBs": round(ba, 1)}}
+                        "act_scale_us": round(ta * 1e3, 1), "act_scale_GBs": round(ba, 1),
+                        "prepare_act_us": round(tp * 1e3, 1), "scale_and_prepare_in_one_pass_us": round(tf * 1e3, 1),
+                        "scale_and_prepare_in_one_pass_GBs": round((2.5 * M * K + 2 * M) / (tf * 1e-3) / 1e9, 1)}}
 
 
 def run_copy_probe(args, torch, B, synth):

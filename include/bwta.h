@@ -214,6 +214,16 @@ int bwta_prepare_weights(const void *W, int64_t ldw, int N, int K, uint32_t *wsi
  */
 int bwta_act_scale(const void *A, int64_t lda, int M, int K, void *s, bwta_stream_t stream);
 
+/*
+ * bwta_act_scale and bwta_prepare_act in one pass over A (the single-pass form of the same
+ * s_A^0 equation followed by the ternary function): writes s_a[m] = fp16(2 * mean_k |A[m, k]|)
+ * (fp16 [M], the same bits as bwta_act_scale) and ternarises every token with its own scale into
+ * `prepared` (see bwta_prepare_act; pass s_a with BWTA_SCALE_VECTOR to bwta_gemm_prepared).  A row
+ * whose scale comes out 0 (all zeros or non-finite) ternarises to zero.  K <= 32768.
+ */
+int bwta_prepare_act_autoscale(const void *A, int64_t lda, int M, int K, void *s_a, void *prepared,
+                               size_t prepared_bytes, bwta_stream_t stream);
+
 /* Human-readable text for a return code (static storage). */
 const char *bwta_strerror(int code);
 /* hipError_t value behind the calling thread's most recent BWTA_ERR_HIP (0 if none). */

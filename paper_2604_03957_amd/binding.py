@@ -24,7 +24,8 @@ EXPORTS = ["bwta_plane_row_words", "bwta_workspace_bytes", "bwta_quantize_pack_a
            "bwta_pack_weights", "bwta_gemm", "bwta_linear", "bwta_strerror", "bwta_last_hip_error",
            "bwta_set_path", "bwta_get_path", "bwta_auto_path", "bwta_version", "bwta_set_tile",
            "bwta_prepared_bytes", "bwta_prepare_act", "bwta_gemm_prepared", "bwta_gemm_grouped",
-           "bwta_quantize_pack_bool", "bwta_matmul_tt", "bwta_prepare_weights", "bwta_act_scale"]
+           "bwta_quantize_pack_bool", "bwta_matmul_tt", "bwta_prepare_weights", "bwta_act_scale",
+           "bwta_prepare_act_autoscale"]
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -74,6 +75,8 @@ _lib.bwta_prepare_weights.restype = _c.c_int
 _lib.bwta_prepare_weights.argtypes = [_P, _c.c_int64, _c.c_int, _c.c_int, _P, _P, _P]
 _lib.bwta_act_scale.restype = _c.c_int
 _lib.bwta_act_scale.argtypes = [_P, _c.c_int64, _c.c_int, _c.c_int, _P, _P]
+_lib.bwta_prepare_act_autoscale.restype = _c.c_int
+_lib.bwta_prepare_act_autoscale.argtypes = [_P, _c.c_int64, _c.c_int, _c.c_int, _P, _P, _c.c_size_t, _P]
 _lib.bwta_strerror.restype = _c.c_char_p
 _lib.bwta_strerror.argtypes = [_c.c_int]
 _lib.bwta_last_hip_error.restype = _c.c_int
@@ -245,6 +248,12 @@ def bwta_prepare_act(A, s_a, prepared, *, M, K, lda=None, a_scale_mode=None, pre
     lda = K if lda is None else lda
     _check(_lib.bwta_prepare_act(_ptr(A), lda, _ptr(s_a), _mode(s_a, a_scale_mode), M, K, _ptr(prepared),
                                  _nbytes(prepared, prepared_bytes), _stream(stream)))
+
+
+def bwta_prepare_act_autoscale(A, s_a, prepared, *, M, K, lda=None, prepared_bytes=None, stream=None):
+    lda = K if lda is None else lda
+    _check(_lib.bwta_prepare_act_autoscale(_ptr(A), lda, M, K, _ptr(s_a), _ptr(prepared),
+                                           _nbytes(prepared, prepared_bytes), _stream(stream)))
 
 
 def bwta_gemm_prepared(prepared, wsign, s_a, s_w, acc, out, *, M, N, K, ldo=None, a_scale_mode=None,

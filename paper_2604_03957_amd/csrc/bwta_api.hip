@@ -195,6 +195,24 @@ int bwta_prepare_act(const void *A, int64_t lda, const void *s_a, int a_scale_mo
     return hip_result(bwta::launch_quantize_pack(A, BWTA_DTYPE_FP16, lda, sa, M, K, mask, sign, nullptr, st));
 }
 
+int bwta_prepare_act_autoscale(const void *A, int64_t lda, int M, int K, void *s_a, void *prepared,
+                               size_t prepared_bytes, bwta_stream_t stream)
+{
+    if (M < 0 || K < 0 || (M > 0 && K == 0)) return BWTA_ERR_SHAPE;
+    if (M == 0) return BWTA_OK;
+    if (lda < K) return BWTA_ERR_SHAPE;
+    if (K > 32768) return BWTA_ERR_UNSUPPORTED;  // a token row is held in one workgroup's registers
+    if (!A || !s_a) return BWTA_ERR_NULL;
+    if (!aligned(A, 2) || !aligned(s_a, 2)) return BWTA_ERR_ALIGN;
+    if (!prepared || prepared_bytes < bwta_prepared_bytes(M, K)) return BWTA_ERR_WORKSPACE;
+    if (!aligned(prepared, 256)) return BWTA_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    uint32_t *mask = (uint32_t *)prepared;
+    uint32_t *sign = (uint32_t *)((char *)prepared + plane_bytes(M, K));
+    uint32_t *frag = fp4_uses_fragments(M, K) ? (uint32_t *)((char *)prepared + 2 * plane_bytes(M, K)) : nullptr;
+    return hip_result(bwta::launch_act_scale_quantize(A, lda, M, K, (uint16_t *)s_a, frag, mask, sign, st));
+}
+
 int bwta_gemm_prepared(const void *prepared, size_t prepared_bytes, const uint32_t *wsign, int M, int N, int K,
                        const void *s_a, int a_scale_mode, const void *s_w, int w_scale_mode, int32_t *acc,
                        void *out, int64_t ldo, bwta_stream_t stream)

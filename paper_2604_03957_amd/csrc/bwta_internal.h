@@ -66,6 +66,13 @@ void set_gemv_tile(int g, int nch);
 hipError_t launch_gemm_fp4(const GemmArgs &g, uint32_t *frag, bool frag_ready, hipStream_t st);
 hipError_t launch_quantize_to_fp4(const void *A, int64_t lda, ScaleArg s_a, int M, int K, uint32_t *frag,
                                   hipStream_t st);
+hipError_t launch_act_scale_quantize(const void *A, int64_t lda, int M, int K, uint16_t *s_out, uint32_t *frag,
+                                     uint32_t *mask, uint32_t *sign, hipStream_t st);
+
+// Fragment buffer geometry of the FP4 tiled kernel: [row block of 32][k step of 64][lane][4 dwords],
+// padded with zeros to a multiple of 8 row blocks and 8 k steps.
+inline int fp4_rb_pad(int M) { return ((M + 31) / 32 + 7) / 8 * 8; }
+inline int fp4_s_pad(int rw) { return (rw / 2 + 7) / 8 * 8; }
 
 // ---- device helpers -------------------------------------------------------------------------
 
@@ -74,6 +81,42 @@ __device__ __forceinline__ float half_bits_to_float(uint16_t h)
     _Float16 f;
     __builtin_memcpy(&f, &h, 2);
     return (float)f;
+}
+
+// Which k step and lane half consume plane word q (identical rule in the converter and the GEMM):
+// words are taken in groups of 8 (one 256-k chunk); word j of a group feeds step 2*(j/4) + j%2
+// of the chunk on lane half (j%4)/2.
+__device__ __forceinline__ void word_slot(int q, int &step, int &half)
+{
+    const int c = q >> 3, j = q & 7;
+    step = 4 * c + 2 * (j >> 2) + (j & 1);
+    half = (j & 3) >> 1;
+}
+
+// 8 fp16 values of one row (lane j of a quad holds elements 8 j .. 8 j + 7 of a 32-element word) ->
+// the dword this lane contributes to the word's fragment: nibble i of dword d holds element
+// 4 i + d (bit 1 = non-zero, bit 3 = negative).  Compares are exact in fp32; NaN thresholds (invalid
+// scale) and NaN values fail both.
+__device__ __forceinline__ uint32_t fragment_dword(const uint4 &x, float hthr, float nthr, int j)
+{
+    const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+    uint32_t V = 0;  // byte d = nibbles of elements d (low) and d + 4 (high): mask -> bit 1, sign -> bit 3
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float a = half_bits_to_float((uint16_t)(w[e >> 1] >> (16 * (e & 1))));
+        uint32_t sel = a >= hthr ? 1u : 0u;  // mask bit; NaN fails both compares
+        sel = a < nthr ? 5u : sel;           // mask bit and, two places up, the sign bit
+        const int base = 8 * (e & 3) + 4 * (e >> 2);
+        V = (sel << (base + 1)) | V;
+    }
+    // quad byte transpose: lane d of the quad collects byte d of every lane -> dword d of the word
+    const uint32_t x0 = __builtin_amdgcn_mov_dpp(V, 0x00, 0xf, 0xf, true);  // quad_perm [0,0,0,0]
+    const uint32_t x1 = __builtin_amdgcn_mov_dpp(V, 0x55, 0xf, 0xf, true);  // [1,1,1,1]
+    const uint32_t x2 = __builtin_amdgcn_mov_dpp(V, 0xaa, 0xf, 0xf, true);  // [2,2,2,2]
+    const uint32_t x3 = __builtin_amdgcn_mov_dpp(V, 0xff, 0xf, 0xf, true);  // [3,3,3,3]
+    const uint32_t sh = 8 * j;
+    return ((x0 >> sh) & 0xffu) | (((x1 >> sh) & 0xffu) << 8) | (((x2 >> sh) & 0xffu) << 16) |
+                       (((x3 >> sh) & 0xffu) << 24);
 }
 
 __device__ __forceinline__ float load_scale(const ScaleArg &s, int row)

@@ -26,16 +26,6 @@ namespace {
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-// Which k step and lane half consume plane word q (identical rule in the converter and the GEMM):
-// words are taken in groups of 8 (one 256-k chunk); word j of a group feeds step 2*(j/4) + j%2
-// of the chunk on lane half (j%4)/2.
-__device__ __forceinline__ void word_slot(int q, int &step, int &half)
-{
-    const int c = q >> 3, j = q & 7;
-    step = 4 * c + 2 * (j >> 2) + (j & 1);
-    half = (j & 3) >> 1;
-}
-
 // planes -> E2M1 fragments.  A workgroup converts 32 rows x 32 words: plane rows are read with
 // coalesced 128-bit loads, the nibble dwords are regrouped through LDS, and the 16 KiB of
 // fragments it produces (16 k steps of one row block) leave as one contiguous run.  The buffer
@@ -76,32 +66,6 @@ __global__ __launch_bounds__(256) void k_planes_to_fp4(const uint32_t *__restric
         const int idx = t + 256 * k;  // 16-byte piece of the 16 KiB output run: slot idx/32, row idx%32
         if (16 * wc + (idx >> 6) < s_pad) dst[idx] = tile[(idx >> 5) * 33 + (idx & 31)];
     }
-}
-
-// 8 fp16 values of one row (lane j of a quad holds elements 8 j .. 8 j + 7 of a 32-element word) ->
-// the dword this lane contributes to the word's fragment: nibble i of dword d holds element
-// 4 i + d (bit 1 = non-zero, bit 3 = negative).  Compares are exact in fp32; NaN thresholds (invalid
-// scale) and NaN values fail both.
-__device__ __forceinline__ uint32_t fragment_dword(const uint4 &x, float hthr, float nthr, int j)
-{
-    const uint32_t w[4] = {x.x, x.y, x.z, x.w};
-    uint32_t V = 0;  // byte d = nibbles of elements d (low) and d + 4 (high): mask -> bit 1, sign -> bit 3
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const float a = half_bits_to_float((uint16_t)(w[e >> 1] >> (16 * (e & 1))));
-        uint32_t sel = a >= hthr ? 1u : 0u;  // mask bit; NaN fails both compares
-        sel = a < nthr ? 5u : sel;           // mask bit and, two places up, the sign bit
-        const int base = 8 * (e & 3) + 4 * (e >> 2);
-        V = (sel << (base + 1)) | V;
-    }
-    // quad byte transpose: lane d of the quad collects byte d of every lane -> dword d of the word
-    const uint32_t x0 = __builtin_amdgcn_mov_dpp(V, 0x00, 0xf, 0xf, true);  // quad_perm [0,0,0,0]
-    const uint32_t x1 = __builtin_amdgcn_mov_dpp(V, 0x55, 0xf, 0xf, true);  // [1,1,1,1]
-    const uint32_t x2 = __builtin_amdgcn_mov_dpp(V, 0xaa, 0xf, 0xf, true);  // [2,2,2,2]
-    const uint32_t x3 = __builtin_amdgcn_mov_dpp(V, 0xff, 0xf, 0xf, true);  // [3,3,3,3]
-    const uint32_t sh = 8 * j;
-    return ((x0 >> sh) & 0xffu) | (((x1 >> sh) & 0xffu) << 8) | (((x2 >> sh) & 0xffu) << 16) |
-                       (((x3 >> sh) & 0xffu) << 24);
 }
 
 // fp16 activations -> E2M1 fragments in one pass (ternarise by the paper's threshold rule and
@@ -678,8 +642,6 @@ static int g_linear_fused_r = 0;
 
 }  // namespace
 
-static int fp4_rb_pad(int M) { return ((M + 31) / 32 + 7) / 8 * 8; }
-static int fp4_s_pad(int rw) { return (rw / 2 + 7) / 8 * 8; }
 
 size_t gemm_fp4_frag_bytes(int M, int K)
 {

@@ -450,6 +450,70 @@ __global__ __launch_bounds__(NT) void k_act_scale(const uint16_t *__restrict__ A
     if (threadIdx.x == 0) s[m] = double_to_half_bits((double)S / ((double)K * 8388608.0));  // 2 S / (K 2^24)
 }
 
+// The same scale and, from the same registers, the ternarised row: one pass over A where
+// bwta_act_scale followed by bwta_prepare_act makes two.  FRAG: E2M1 fragments for the tiled
+// matrix-core kernel (the grid also covers the padding rows of the last row blocks, and the threads
+// the padding k steps: they write the zeros the product relies on); otherwise the two bit planes.
+// Thread t's group g is elements 8 (t + NT g) ..: the four lanes of a hardware quad hold one
+// 32-element plane word, which both output forms assemble inside the quad.
+template <int NG, int NT, bool FRAG>
+__global__ __launch_bounds__(NT) void k_act_scale_quantize(const uint16_t *__restrict__ A, int64_t lda, int M, int K,
+                                                           int rw, uint16_t *__restrict__ s_out,
+                                                           uint32_t *__restrict__ frag, int s_pad,
+                                                           uint32_t *__restrict__ mask, uint32_t *__restrict__ sign,
+                                                           int whole)
+{
+    __shared__ long long s_ll[NT / 64];
+    const int m = blockIdx.x, c8 = (K + 7) / 8;
+    uint4 x[NG];
+    if (m < M) {
+        load_row_groups<NG, NT>(A + (int64_t)m * lda, K, c8, whole != 0, x);
+    } else {
+#pragma unroll
+        for (int g = 0; g < NG; ++g) x[g] = make_uint4(0, 0, 0, 0);
+    }
+    double part = 0.0;
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {  // elements past K were loaded as +0 and add nothing
+            const uint16_t h = half_of(x[g], i) & 0x7fff;
+            const float f = h < 0x7c00 ? half_bits_to_float(h) : 0.0f;  // NaN / Inf stay out
+            part += (double)f;
+        }
+    }
+    const long long S = block_sum<NT>(double_units(part), s_ll);
+    const uint16_t s_bits = double_to_half_bits((double)S / ((double)K * 8388608.0));  // 2 S / (K 2^24)
+    if (threadIdx.x == 0 && m < M) s_out[m] = s_bits;
+    // thresholds +-0.5 s, exact in fp32; an all-zero (or all non-finite) row has s = 0, an invalid
+    // scale: NaN thresholds fail every compare and the row ternarises to zero
+    const float sc = half_bits_to_float(s_bits);
+    const bool ok = sc > 0.0f && sc < __builtin_inff();
+    const float hthr = ok ? 0.5f * sc : __builtin_nanf(""), nthr = -hthr;
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+        const int c = (int)threadIdx.x + NT * g, q = c >> 2, j = c & 3;
+        if (FRAG) {
+            const uint32_t D = fragment_dword(x[g], hthr, nthr, j);
+            int step, half;
+            word_slot(q, step, half);
+            if (step < s_pad)
+                frag[(((int64_t)(m >> 5) * s_pad + step) * 64 + half * 32 + (m & 31)) * 4 + j] = D;
+        } else {
+            uint16_t v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = half_of(x[g], i);
+            const TernaryBits tb = ternary_bits_fp16(v, 8, 0.5f * sc, ok);
+            const uint32_t mw = quad_word(tb.nz, lane), sw = quad_word(tb.neg, lane);
+            if (q < rw && j == 0) {
+                mask[(int64_t)m * rw + q] = mw;
+                sign[(int64_t)m * rw + q] = sw;
+            }
+        }
+    }
+}
+
 // mask plane of a binary (+-1) activation matrix: every element is non-zero; pad bits stay zero
 __global__ __launch_bounds__(kThreads) void k_full_mask(uint32_t *__restrict__ mask, int64_t words, int rw, int K)
 {
@@ -501,6 +565,31 @@ hipError_t launch_act_scale(const void *A, int64_t lda, int M, int K, uint16_t *
     }
     BWTA_SCALE(1, 256) BWTA_SCALE(2, 256) BWTA_SCALE(4, 256) BWTA_SCALE(8, 256) BWTA_SCALE(4, 1024)
 #undef BWTA_SCALE
+    return hipErrorInvalidValue;
+}
+
+// scale + ternarised operand in one pass; frag != nullptr selects fragments, else planes
+hipError_t launch_act_scale_quantize(const void *A, int64_t lda, int M, int K, uint16_t *s_out, uint32_t *frag,
+                                     uint32_t *mask, uint32_t *sign, hipStream_t st)
+{
+    if (M == 0) return hipSuccess;
+    const int rw = 4 * ((K + 127) / 128);
+    const int whole = (((uintptr_t)A % 16) == 0 && (lda % 8) == 0 && (K % 8) == 0) ? 1 : 0;
+    const int s_pad = fp4_s_pad(rw);
+    const int rows = frag ? 32 * fp4_rb_pad(M) : M;
+    const int c8 = frag ? 8 * s_pad : 4 * rw;  // 128-bit groups a row's threads must cover (padding included)
+#define BWTA_SQ(NG_, NT_)                                                                                          \
+    if (c8 <= NG_ * NT_) {                                                                                         \
+        if (frag)                                                                                                  \
+            hipLaunchKernelGGL((k_act_scale_quantize<NG_, NT_, true>), dim3(rows), dim3(NT_), 0, st,                \
+                               (const uint16_t *)A, lda, M, K, rw, s_out, frag, s_pad, mask, sign, whole);         \
+        else                                                                                                       \
+            hipLaunchKernelGGL((k_act_scale_quantize<NG_, NT_, false>), dim3(rows), dim3(NT_), 0, st,               \
+                               (const uint16_t *)A, lda, M, K, rw, s_out, frag, s_pad, mask, sign, whole);         \
+        return hipGetLastError();                                                                                  \
+    }
+    BWTA_SQ(1, 256) BWTA_SQ(2, 256) BWTA_SQ(4, 256) BWTA_SQ(8, 256) BWTA_SQ(4, 1024)
+#undef BWTA_SQ
     return hipErrorInvalidValue;
 }
 

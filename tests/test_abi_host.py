@@ -148,3 +148,14 @@ def test_weight_preparation_entry_points_reject_bad_arguments():
     assert _code(sc, FAKE, FAKE, **dict(kw, lda=8)) == B.ERR_SHAPE
     assert _code(sc, FAKE, FAKE, **dict(kw, K=40000)) == B.ERR_UNSUPPORTED
     sc(FAKE, FAKE, **dict(kw, M=0))
+    au = B.bwta_prepare_act_autoscale
+    kw = dict(M=4, K=256, stream=0, prepared_bytes=B.prepared_bytes(4, 256))
+    assert _code(au, None, FAKE, FAKE, **kw) == B.ERR_NULL
+    assert _code(au, FAKE, None, FAKE, **kw) == B.ERR_NULL
+    assert _code(au, FAKE, FAKE + 1, FAKE, **kw) == B.ERR_ALIGN
+    assert _code(au, FAKE, FAKE, FAKE + 16, **kw) == B.ERR_ALIGN
+    assert _code(au, FAKE, FAKE, FAKE, **dict(kw, lda=8)) == B.ERR_SHAPE
+    assert _code(au, FAKE, FAKE, FAKE, **dict(kw, prepared_bytes=16)) == B.ERR_WORKSPACE
+    assert _code(au, FAKE, FAKE, None, **kw) == B.ERR_WORKSPACE
+    assert _code(au, FAKE, FAKE, FAKE, **dict(kw, K=40000, prepared_bytes=1 << 30)) == B.ERR_UNSUPPORTED
+    au(FAKE, FAKE, FAKE, **dict(kw, M=0))

@@ -86,3 +86,40 @@ def test_prepared_weights_feed_the_linear_layer():
     mask, sign, _ = oracle.pack_act(t)
     acc, out = gpu_gemm(mask, sign, ws, s_a, sw.cpu().numpy(), M, N, K)
     assert np.array_equal(acc, want_acc) and same_half(out, want)
+
+
+@pytest.mark.parametrize("path", [B.PATH_AUTO, B.PATH_POPC, B.PATH_FP4])
+@pytest.mark.parametrize("M,N,K,lda", [(5, 40, 40, 40), (64, 70, 768, 768), (33, 50, 300, 304), (130, 96, 1001, 1003),
+                                       (257, 130, 4096, 4096), (300, 64, 11008, 11008), (200, 33, 520, 528)])
+def test_scale_and_ternarise_in_one_pass(M, N, K, lda, path):
+    """bwta_prepare_act_autoscale: the token scales it writes are the oracle's act_scale (to the
+    floating-point bar, and bit for bit on these inputs), and the operand it prepares, fed to
+    bwta_gemm_prepared with those scales, gives the oracle's linear layer exactly.  Both operand
+    forms (bit planes below 129 tokens and on the popcount path, matrix-core fragments above),
+    ragged and strided rows, NaN / Inf entries, an all-zero token (scale 0: the token is zero)."""
+    _say("scale + ternarise", M, N, K, lda, "path", path)
+    A = np.ascontiguousarray(synth.gaussian_outlier_activations(90 + M, 1, M, lda))
+    A[0, :min(K, 4)] = np.array([np.nan, np.inf, 65504.0, 6e-8], np.float16)[:min(K, 4)]
+    A[2, :] = 0
+    Ak = np.ascontiguousarray(A[:, :K])
+    s_want = oracle.act_scale(Ak)
+    assert s_want[2] == 0
+    w = synth.binary_pm1(91, M + N, (N, K))
+    s_w = synth.scales(91, 3, N)
+    _, _, want = oracle.linear(Ak, s_want, w, s_w)
+    B.set_path(path)
+    try:
+        s = torch.full((M,), float("nan"), dtype=torch.float16, device=DEV)
+        prep = torch.empty(B.prepared_bytes(M, K), dtype=torch.uint8, device=DEV)
+        out = torch.full((M, N), 7.0, dtype=torch.float16, device=DEV)
+        ws = torch.empty((N, B.plane_row_words(K)), dtype=torch.int32, device=DEV)
+        B.bwta_pack_weights(dev(w), ws, N=N, K=K)
+        B.bwta_prepare_act_autoscale(dev(A), s, prep, M=M, K=K, lda=lda)
+        B.bwta_gemm_prepared(prep, ws, s, dev(s_w), None, out, M=M, N=N, K=K)
+        torch.cuda.synchronize()
+    finally:
+        B.set_path(B.PATH_AUTO)
+    got_s = s.cpu().numpy()
+    assert max_rel_err(got_s.reshape(1, -1), s_want.reshape(1, -1)) <= 1e-3
+    assert same_half(got_s, s_want)
+    assert same_half(out.cpu().numpy(), want)
