@@ -167,9 +167,22 @@ def cpu_baseline_c2(cfgs, target_s=12.0):
         dt = time.perf_counter() - t0
         if dt >= target_s or passes >= 50:
             break
-    return {"value": round(ops_per_pass * passes / dt / 1e12, 5), "unit": "TOPS", "cores": threads,
-            "kind": "oracle", "sample": "%d full passes of the same two layers (all %d tokens), %.1f s"
-            % (passes, cfgs[0]["M"], dt)}
+    out = {"value": round(ops_per_pass * passes / dt / 1e12, 5), "unit": "TOPS", "cores": threads,
+           "kind": "oracle", "sample": "%d full passes of the same two layers (all %d tokens), %.1f s"
+           % (passes, cfgs[0]["M"], dt)}
+    # the same oracle on one thread, on the first 256 tokens of both layers (a few seconds)
+    oracle.set_num_threads(1)
+    try:
+        rows = 256
+        t1 = time.perf_counter()
+        for c in cfgs:
+            oracle.linear(np.ascontiguousarray(c["A"][:rows]), c["s_a"][:rows], c["w"], c["s_w"])
+        d1 = time.perf_counter() - t1
+        out["single_thread_value"] = round(sum(2.0 * rows * c["N"] * c["K"] for c in cfgs) / d1 / 1e12, 5)
+        out["single_thread_sample"] = "one pass over the first %d tokens of both layers, %.1f s" % (rows, d1)
+    finally:
+        oracle.set_num_threads(threads)
+    return out
 
 
 def run_c2(args, torch, B, synth):
