@@ -15,6 +15,9 @@
 // the widening that cheap.
 // The weights are the instruction's first operand, so a lane ends up with 4 consecutive output
 // channels of one token: the fp16 epilogue packs them and moves 8 bytes per LDS write.
+//
+// Kernels here: k_planes_to_fp4 / k_quantize_to_fp4 (bit planes / fp16 activations -> fragments),
+// k_gemm_fp4 (the tiled product) and k_linear_fused (ternarise + product in one launch, short K).
 #include <type_traits>
 
 #include "bwta_internal.h"
