@@ -544,6 +544,33 @@ def run_prep(args, torch, B, synth):
                         "scale_and_prepare_in_one_pass_GBs": round((2.5 * M * K + 2 * M) / (tf * 1e-3) / 1e9, 1)}}
 
 
+def run_short_k(args, torch, B, synth):
+    """bwta_linear on short-K layers (encoder attention projections and the like), as one launch
+    (the dispatcher's choice where it pays) and as ternarise + product (forced with the tuning hook)."""
+    base = synth.config2("up")
+    rows = []
+    for (M, N, K) in [(4096, 768, 768), (4096, 768, 256), (4096, 3072, 256), (1024, 768, 768), (4096, 3072, 768)]:
+        A = np.ascontiguousarray(np.tile(base["A"], (1, 2))[:M, :K])
+        c = dict(M=M, N=N, K=K, A=A, s_a=base["s_a"][:M], w=synth.binary_pm1(8, N + K, (N, K)), s_w=synth.scales(8, 4, N),
+                 name="short_k")
+        L = Layer(c, torch, B, from_fp16=True)
+        B.set_tile(900)
+        two = _event_ms(torch, lambda: L.linear(B), args.steps, args.warmup)
+        B.set_tile(0)
+        auto = _event_ms(torch, lambda: L.linear(B), args.steps, args.warmup)
+        B.set_tile(901)
+        one = _event_ms(torch, lambda: L.linear(B), args.steps, args.warmup)
+        B.set_tile(0)
+        rows.append({"M": M, "N": N, "K": K, "two_kernels_us": round(two * 1e3, 2), "one_launch_us": round(one * 1e3, 2),
+                     "dispatcher_us": round(auto * 1e3, 2), "dispatcher_TOPS": round(L.ops / (auto * 1e-3) / 1e12, 1)})
+        del L
+    mean = float(np.mean([r["dispatcher_us"] for r in rows]))
+    return {"metric": "BWTA linear latency on short-K layers", "value": round(mean, 2), "unit": "us", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(mean / 1e3, 6), "higher_is_better": False,
+            "scaling": "weak", "vs_baseline": None, "dtype": "fp4 (E2M1 operands, exact integer result in fp32)",
+            "data": "synthetic", "config": {"workload": "short_k: bwta_linear, fp16 in/out, K <= 768"}, "kernels": rows}
+
+
 def run_copy_probe(args, torch, B, synth):
     """A plain device-to-device copy of known size (256 MiB), used to calibrate the FETCH_SIZE /
     WRITE_SIZE counters that the traffic figures in profiles/ are scaled by."""
@@ -565,7 +592,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=None,
                     help="untimed steps first (default 1000 for c2_ffn, about 30 ms: the clock ramp of an "
                          "idle GPU; 20 otherwise, where every timed region settles the clock itself)")
-    ap.add_argument("--workload", default="c2_ffn", choices=["c2_ffn", "c1_tiny", "c3_prefill", "c4_decode", "c5_block", "attn", "prep", "copy_probe"])
+    ap.add_argument("--workload", default="c2_ffn", choices=["c2_ffn", "c1_tiny", "c3_prefill", "c4_decode", "c5_block", "attn", "prep", "short_k", "copy_probe"])
     ap.add_argument("--decode-matrices", type=int, default=64)
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--graph", action="store_true",
@@ -588,7 +615,8 @@ def main():
     from paper_2604_03957_amd import synth
     torch.cuda.set_device(0)
     run = {"c2_ffn": run_c2, "c1_tiny": run_c1, "c3_prefill": run_c3, "c4_decode": run_c4,
-           "c5_block": run_c5, "attn": run_attn, "prep": run_prep, "copy_probe": run_copy_probe}[args.workload]
+           "c5_block": run_c5, "attn": run_attn, "prep": run_prep, "short_k": run_short_k,
+           "copy_probe": run_copy_probe}[args.workload]
     out = run(args, torch, B, synth)
     print(json.dumps(out), flush=True)
 
