@@ -204,6 +204,7 @@ def run_c2(args, torch, B, synth):
     if args.graph:
         graph = _graph_of(torch, step, check)
         run = graph.replay
+    _settle(torch, run)  # untimed: brings an idle GPU's clock up, whatever --warmup was asked for
     for _ in range(args.warmup):
         run()
     torch.cuda.synchronize()
@@ -246,7 +247,8 @@ def run_c2(args, torch, B, synth):
            "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
            "vs_baseline": None, "dtype": "fp4 (E2M1 operands, exact integer result in fp32)", "data": "synthetic",
            "config": {"workload": "c2_ffn: M=4096 (32x128 tokens), K=768->N=3072 and K=3072->N=768, fp16 in/out",
-                      "path": "full (bwta_linear x2 per step)", "launch": "hip graph replay" if args.graph else "eager"},
+                      "path": "full (bwta_linear x2 per step)", "launch": "hip graph replay" if args.graph else "eager",
+                      "clock_settle_ms": int(SETTLE_S * 1e3)},
            "roofline": roofline, "kernels": kern}
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline_c2(cfgs)
