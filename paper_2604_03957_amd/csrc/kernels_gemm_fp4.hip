@@ -29,20 +29,23 @@ namespace {
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-// planes -> E2M1 fragments.  A workgroup converts 32 rows x 32 words: plane rows are read with
-// coalesced 128-bit loads, the nibble dwords are regrouped through LDS, and the 16 KiB of
-// fragments it produces (16 k steps of one row block) leave as one contiguous run.  The buffer
+// planes -> E2M1 fragments.  A workgroup converts 32 rows x NW words: plane rows are read with
+// coalesced 128-bit loads, the nibble dwords are regrouped through LDS, and the NW / 2 KiB of
+// fragments it produces (NW / 2 k steps of one row block) leave as one contiguous run.  The buffer
 // is padded with zeros to a multiple of 8 row blocks and 8 k steps so that the GEMM never has
-// to guard an activation load.
-__global__ __launch_bounds__(256) void k_planes_to_fp4(const uint32_t *__restrict__ mask,
-                                                       const uint32_t *__restrict__ sign, int M, int rw,
-                                                       int s_pad, uint32_t *__restrict__ frag)
+// to guard an activation load.  The kernel is one memory round trip long, so small problems take
+// small NW: more workgroups, and every compute unit has requests in flight from the start.
+template <int NW>  // 8, 16 or 32 plane words per workgroup of 8 NW threads
+__global__ __launch_bounds__(8 * NW) void k_planes_to_fp4(const uint32_t *__restrict__ mask,
+                                                          const uint32_t *__restrict__ sign, int M, int rw,
+                                                          int s_pad, uint32_t *__restrict__ frag)
 {
-    __shared__ uint4 tile[32 * 33];  // [slot = step_local * 2 + half][row], one spare row of skew
+    __shared__ uint4 tile[NW * 33];  // [slot = step_local * 2 + half][row], one spare row of skew
+    constexpr int NT = 8 * NW, QPR = NW / 4;  // threads; 128-bit pieces per row
     const int t = threadIdx.x;
-    const int rb = blockIdx.y, wc = blockIdx.x;  // row block, group of 32 words (16 k steps)
-    const int row = t >> 3, q4 = t & 7;
-    const int m = rb * 32 + row, q = 32 * wc + 4 * q4;
+    const int rb = blockIdx.y, wc = blockIdx.x;  // row block, group of NW words (NW / 2 k steps)
+    const int row = t / QPR, q4 = t % QPR;
+    const int m = rb * 32 + row, q = NW * wc + 4 * q4;
     uint4 mk4 = make_uint4(0, 0, 0, 0), sg4 = mk4;
     if (m < M && q < rw) {
         mk4 = *(const uint4 *)(mask + (int64_t)m * rw + q);
@@ -59,15 +62,15 @@ __global__ __launch_bounds__(256) void k_planes_to_fp4(const uint32_t *__restric
         o.z = ((sg << 1) & 0x88888888u) | ((mk >> 1) & 0x22222222u);
         o.w = (sg & 0x88888888u) | ((mk >> 2) & 0x22222222u);
         int step, half;
-        word_slot(4 * q4 + w, step, half);  // local word index 0..31 -> local step 0..15
+        word_slot(4 * q4 + w, step, half);  // local word index 0..NW-1 -> local step 0..NW/2-1
         tile[(step * 2 + half) * 33 + row] = o;
     }
     __syncthreads();
-    uint4 *dst = (uint4 *)frag + ((int64_t)rb * s_pad + 16 * wc) * 64;
+    uint4 *dst = (uint4 *)frag + ((int64_t)rb * s_pad + (NW / 2) * wc) * 64;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-        const int idx = t + 256 * k;  // 16-byte piece of the 16 KiB output run: slot idx/32, row idx%32
-        if (16 * wc + (idx >> 6) < s_pad) dst[idx] = tile[(idx >> 5) * 33 + (idx & 31)];
+        const int idx = t + NT * k;  // 16-byte piece of the output run: slot idx/32, row idx%32
+        if ((NW / 2) * wc + (idx >> 6) < s_pad) dst[idx] = tile[(idx >> 5) * 33 + (idx & 31)];
     }
 }
 
@@ -726,8 +729,16 @@ hipError_t launch_gemm_fp4(const GemmArgs &g, uint32_t *frag, bool frag_ready, h
 {
     const int rb_pad = fp4_rb_pad(g.M), s_pad = fp4_s_pad(g.rw);
     if (!frag_ready) {
-        hipLaunchKernelGGL(k_planes_to_fp4, dim3((s_pad + 15) / 16, rb_pad), dim3(256), 0, st, g.mask, g.sign, g.M,
-                           g.rw, s_pad, frag);
+        const int64_t wgs32 = (int64_t)((s_pad + 15) / 16) * rb_pad;  // workgroups at 32 words each
+        if (wgs32 >= 1024)
+            hipLaunchKernelGGL(k_planes_to_fp4<32>, dim3((s_pad + 15) / 16, rb_pad), dim3(256), 0, st, g.mask, g.sign, g.M,
+                               g.rw, s_pad, frag);
+        else if (2 * wgs32 >= 1024)
+            hipLaunchKernelGGL(k_planes_to_fp4<16>, dim3((s_pad + 7) / 8, rb_pad), dim3(128), 0, st, g.mask, g.sign, g.M,
+                               g.rw, s_pad, frag);
+        else
+            hipLaunchKernelGGL(k_planes_to_fp4<8>, dim3((s_pad + 3) / 4, rb_pad), dim3(64), 0, st, g.mask, g.sign, g.M,
+                               g.rw, s_pad, frag);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
