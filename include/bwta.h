@@ -103,7 +103,8 @@ int bwta_pack_weights(const void *W, int w_dtype, int64_t ldw, int N, int K, uin
  *   mask, sign  u32 [M, row_words]; sign bits under a zero mask bit are ignored.  mask == NULL
  *               means binary (+-1) activations, every element non-zero: the W1A1 "Binary Linear"
  *               special case acc = K - 2 * popc(sign_m ^ wsign_n); pack such activations with
- *               bwta_pack_weights (the sign packer).  The mask is then built in the workspace.
+ *               bwta_pack_weights (the sign packer).  No mask plane is read; kernels that need
+ *               one get it built in the workspace.
  *   wsign       u32 [N, row_words].
  *   acc         optional out, int32 [M, N] dense (leading dimension N).
  *   out         optional out, fp16 [M, ldo], ldo >= N.  At least one of acc / out.

@@ -128,10 +128,13 @@ int bwta_gemm(const uint32_t *mask, const uint32_t *sign, const uint32_t *wsign,
     if (acc && !aligned(acc, 4)) return BWTA_ERR_ALIGN;
     if (!workspace || workspace_bytes < bwta_workspace_bytes(M, N, K)) return BWTA_ERR_WORKSPACE;
     if (!aligned(workspace, 256)) return BWTA_ERR_ALIGN;
-    if (!mask) {  // binary (+-1) activations: the W1A1 layer.  Every element is non-zero.
+    // binary (+-1) activations: the W1A1 layer.  Every element is non-zero.  The tiled matrix-core
+    // path synthesises the mask while it converts the sign plane (no mask plane is written or read);
+    // the other kernels get a full mask built in the workspace, whose mask area is otherwise unused here.
+    if (!mask && !fp4_uses_fragments(M, K)) {
         int rcm = hip_result(bwta::launch_full_mask((uint32_t *)workspace, M, K, (hipStream_t)stream));
         if (rcm != BWTA_OK) return rcm;
-        mask = (const uint32_t *)workspace;  // the mask area of the workspace is otherwise unused here
+        mask = (const uint32_t *)workspace;
     }
     bwta::GemmArgs g{mask, sign, wsign, M, N, K, (int)bwta_plane_row_words(K),
                      {(const uint16_t *)s_a, s_a ? a_scale_mode : BWTA_SCALE_NONE},

@@ -37,7 +37,7 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 // small NW: more workgroups, and every compute unit has requests in flight from the start.
 template <int NW>  // 8, 16 or 32 plane words per workgroup of 8 NW threads
 __global__ __launch_bounds__(8 * NW) void k_planes_to_fp4(const uint32_t *__restrict__ mask,
-                                                          const uint32_t *__restrict__ sign, int M, int rw,
+                                                          const uint32_t *__restrict__ sign, int M, int K, int rw,
                                                           int s_pad, uint32_t *__restrict__ frag)
 {
     __shared__ uint4 tile[NW * 33];  // [slot = step_local * 2 + half][row], one spare row of skew
@@ -48,8 +48,18 @@ __global__ __launch_bounds__(8 * NW) void k_planes_to_fp4(const uint32_t *__rest
     const int m = rb * 32 + row, q = NW * wc + 4 * q4;
     uint4 mk4 = make_uint4(0, 0, 0, 0), sg4 = mk4;
     if (m < M && q < rw) {
-        mk4 = *(const uint4 *)(mask + (int64_t)m * rw + q);
         sg4 = *(const uint4 *)(sign + (int64_t)m * rw + q);
+        if (mask) {
+            mk4 = *(const uint4 *)(mask + (int64_t)m * rw + q);
+        } else {  // binary (+-1) activations: every element below K is non-zero, no mask plane is read
+            uint32_t ones[4];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const int left = K - 32 * (q + w);
+                ones[w] = left >= 32 ? 0xffffffffu : (left > 0 ? (1u << left) - 1u : 0u);
+            }
+            mk4 = make_uint4(ones[0], ones[1], ones[2], ones[3]);
+        }
     }
     const uint32_t mks[4] = {mk4.x, mk4.y, mk4.z, mk4.w};
     const uint32_t sgs[4] = {sg4.x, sg4.y, sg4.z, sg4.w};
@@ -732,13 +742,13 @@ hipError_t launch_gemm_fp4(const GemmArgs &g, uint32_t *frag, bool frag_ready, h
         const int64_t wgs32 = (int64_t)((s_pad + 15) / 16) * rb_pad;  // workgroups at 32 words each
         if (wgs32 >= 1024)
             hipLaunchKernelGGL(k_planes_to_fp4<32>, dim3((s_pad + 15) / 16, rb_pad), dim3(256), 0, st, g.mask, g.sign, g.M,
-                               g.rw, s_pad, frag);
+                               g.K, g.rw, s_pad, frag);
         else if (2 * wgs32 >= 1024)
             hipLaunchKernelGGL(k_planes_to_fp4<16>, dim3((s_pad + 7) / 8, rb_pad), dim3(128), 0, st, g.mask, g.sign, g.M,
-                               g.rw, s_pad, frag);
+                               g.K, g.rw, s_pad, frag);
         else
             hipLaunchKernelGGL(k_planes_to_fp4<8>, dim3((s_pad + 3) / 4, rb_pad), dim3(64), 0, st, g.mask, g.sign, g.M,
-                               g.rw, s_pad, frag);
+                               g.K, g.rw, s_pad, frag);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

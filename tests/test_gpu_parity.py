@@ -417,7 +417,7 @@ def test_gemm_grouped_matches_oracle(M, N, K, count, path):
 
 
 @pytest.mark.parametrize("path", [B.PATH_AUTO] + PATHS)
-@pytest.mark.parametrize("M,N,K", [(64, 96, 768), (3, 130, 1000), (130, 70, 129), (16, 257, 4096)])
+@pytest.mark.parametrize("M,N,K", [(64, 96, 768), (3, 130, 1000), (130, 70, 129), (16, 257, 4096), (300, 200, 1000)])
 def test_binary_activations_w1a1(M, N, K, path):
     """mask == NULL: binary (+-1) activations, the W1A1 "Binary Linear" special case
     acc = K - 2 popc(x ^ w); the activation signs are packed with the sign packer."""
