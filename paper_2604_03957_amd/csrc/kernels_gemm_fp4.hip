@@ -203,7 +203,9 @@ __device__ __forceinline__ void store_tile_fp16(const v16f (&acc)[WN][WM], const
     constexpr int PITCH = 32 * WN + 8;  // halfs; 16-byte aligned rows, conflict-free 8-byte writes
     const bool full = (m_wave + 32 * WM <= g.M) && (n_wave + 32 * WN <= g.N) && ((g.ldo & 7) == 0) &&
                       (((uintptr_t)g.out & 15) == 0);
-    constexpr int LPR = 4 * WN, RPI = 64 / LPR;  // lanes per token row (8 halfs each), rows per store
+    // lanes per token row (8 halfs each), rows per store; with three channel blocks 60 of the 64 lanes store
+    constexpr int LPR = 4 * WN, RPI = 64 / LPR;
+    constexpr bool EVEN = RPI * LPR == 64 && 32 % RPI == 0;
 #pragma unroll
     for (int i = 0; i < WM; ++i) {
         const float sa = sa_w[32 * i + r32];
@@ -224,6 +226,7 @@ __device__ __forceinline__ void store_tile_fp16(const v16f (&acc)[WN][WM], const
 #pragma unroll
         for (int rr = 0; rr < 32; rr += RPI) {
             const int row = rr + lane / LPR, c8 = 8 * (lane % LPR);
+            if (!EVEN && (lane >= RPI * LPR || row >= 32)) continue;
             const int mo = m_wave + 32 * i + row, n = n_wave + c8;
             const uint4 q = *(const uint4 *)(strip + row * PITCH + c8);
             uint16_t *dst = g.out + (int64_t)mo * g.ldo + n;
@@ -759,6 +762,7 @@ hipError_t launch_gemm_fp4(const GemmArgs &g, uint32_t *frag, bool frag_ready, h
     case 21: return launch<2, 1, 2, 2, 3, false>(g, frag, s_pad, st);
     case 12: return launch<1, 2, 2, 2, 3, false>(g, frag, s_pad, st);
     case 11: return launch<1, 1, 2, 2, 4, false>(g, frag, s_pad, st);
+    case 13: return launch<1, 3, 4, 1, 2, false>(g, frag, s_pad, st);
     case 2216: return launch<2, 2, 2, 2, 2, false, 1, 16>(g, frag, s_pad, st);
     case 22216: return launch<2, 2, 2, 2, 2, false, 2, 16>(g, frag, s_pad, st);
     case 222: return launch<2, 2, 2, 2, 2, false, 2>(g, frag, s_pad, st);
@@ -769,6 +773,13 @@ hipError_t launch_gemm_fp4(const GemmArgs &g, uint32_t *frag, bool frag_ready, h
     // 192-512 tokens: 7.5-9.4 us against 11.4-12.0 us at K = 4096, 15.8-19.7 against 24-25 at K = 11008).
     const int64_t tiles128 = (int64_t)((g.M + 127) / 128) * ((g.N + 127) / 128);
     if (tiles128 <= 128 && g.K >= 1024) return launch<1, 1, 2, 2, 4, false>(g, frag, s_pad, st);
+    // Between 129 and 255 tiles of 128 x 128 some compute units get no workgroup at all.  If tiles of
+    // 128 x 96 (four wavefronts of 32 x 96) number at most 256, every one of them still runs in the
+    // first round and more compute units take part (measured at M = 4096, N = 768, K = 3072: 192 -> 256
+    // workgroups, 9.7 -> 8.3 us).
+    const int64_t tiles96 = (int64_t)((g.M + 127) / 128) * ((g.N + 95) / 96);
+    if (tiles128 < 256 && tiles96 > tiles128 && tiles96 <= 256 && g.K >= 1024)
+        return launch<1, 3, 4, 1, 2, false>(g, frag, s_pad, st);
     // measured: long K runs best with 2 wavefronts per SIMD (179 registers), short K with 3
     if (g.K >= 2048) return launch<2, 2, 2, 2, 2, false>(g, frag, s_pad, st);
     return launch<2, 2, 2, 2, 3, false>(g, frag, s_pad, st);
