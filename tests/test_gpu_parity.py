@@ -345,6 +345,35 @@ def test_linear_one_launch_short_k(M, N, K, hook):
     assert same_half(out, want)
 
 
+def test_linear_one_launch_scale_modes_and_strides():
+    """The one-launch kernel with layerwise (scalar) scales, with no scales at all, and with strided
+    input and output (nothing written past N)."""
+    M, N, K, lda, ldo = 300, 260, 512, 520, 272
+    A, _ = _activation_case(601, M, lda)
+    w = synth.binary_pm1(34, 1, (N, K))
+    Ak = np.ascontiguousarray(A[:, :K])
+    one_a, one_w = np.array([0.75], np.float16), np.array([1.25], np.float16)
+    ws = torch.empty(B.workspace_bytes(M, N, K), dtype=torch.uint8, device="cuda:0")
+    wsign = gpu_pack_weights(w)
+    B.set_tile(901)
+    B.set_path(B.PATH_FP4)
+    try:
+        for s_a, s_w in ((one_a, one_w), (None, None)):
+            fa = np.full(M, 1.0 if s_a is None else s_a[0], np.float16)
+            fw = np.full(N, 1.0 if s_w is None else s_w[0], np.float16)
+            _, _, want = oracle.linear(Ak, fa, w, fw)
+            out = torch.full((M, ldo), 7.0, dtype=torch.float16, device="cuda:0")
+            B.bwta_linear(dev(A), None if s_a is None else dev(s_a), wsign, None if s_w is None else dev(s_w), out, ws,
+                          M=M, N=N, K=K, lda=lda, ldo=ldo)
+            torch.cuda.synchronize()
+            got = out.cpu().numpy()
+            assert same_half(np.ascontiguousarray(got[:, :N]), want)
+            assert np.all(got[:, N:] == 7.0)
+    finally:
+        B.set_path(B.PATH_AUTO)
+        B.set_tile(0)
+
+
 def test_linear_strided_input_and_output():
     M, N, K, lda, ldo = 50, 72, 520, 528, 80
     A, s = _activation_case(9, M, lda)
