@@ -378,9 +378,25 @@ def run_attn(args, torch, B, synth):
     B.set_path(B.PATH_POPC)
     t_popc = {n: _event_ms(torch, f, steps, 2) for n, f in (("qk", qk), ("att_v", av))}
     B.set_path(B.PATH_AUTO)
+    # Att V with V^T prepared once as matrix-core fragments (the boolean plane then plays the weights'
+    # part in the tiled kernel): same bits, checked here against the planes-in-registers product
+    prep_v = torch.empty(B.prepared_bytes(H * D, S), dtype=torch.uint8, device=dev)
+    ctx2 = torch.zeros_like(ctx)
+
+    def prepare_v():
+        B.bwta_prepare_act(vt, one, prep_v, M=H * D, K=S)
+
+    def av_prepared():
+        B.bwta_matmul_bool_prepared(am, prep_v, s_att, one, ctx2, batch=H, M=S, N=D, K=S)
+
+    av(); prepare_v(); av_prepared(); torch.cuda.synchronize()
+    assert torch.equal(ctx.view(torch.int16), ctx2.view(torch.int16)), "the two Att V products differ"
+    t_prep = {n: _event_ms(torch, f, steps, 2) for n, f in (("prepare_v", prepare_v), ("att_v_prepared", av_prepared))}
     ops = 2.0 * H * S * S * D
     total = sum(t.values())
     kern = {n + "_us": round(v * 1e3, 1) for n, v in t.items()}
+    kern.update({n + "_us": round(v * 1e3, 1) for n, v in t_prep.items()})
+    kern.update(att_v_prepared_TOPS=round(ops / (t_prep["att_v_prepared"] * 1e-3) / 1e12, 1))
     kern.update(qk_TOPS=round(ops / (t["qk"] * 1e-3) / 1e12, 1), att_v_TOPS=round(ops / (t["att_v"] * 1e-3) / 1e12, 1),
                 qk_popc_us=round(t_popc["qk"] * 1e3, 1), att_v_popc_us=round(t_popc["att_v"] * 1e3, 1))
     achieved = 2 * ops / ((t["qk"] + t["att_v"]) * 1e-3) / 1e12

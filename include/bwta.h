@@ -197,6 +197,25 @@ int bwta_matmul_tt(const uint32_t *maskA, const uint32_t *signA, int64_t strideA
                    int64_t ldo, int64_t stride_out, bwta_stream_t stream);
 
 /*
+ * The BWTA_Att rule (bool x ternary, arithmetic Case 2) with the ternary operand prepared once:
+ *   acc[b, m, n] = sum_k A[b, m, k] * B[b, n, k]      A boolean: its plane from
+ *                                                     bwta_quantize_pack_bool, [M, row_words] per
+ *                                                     batch entry, entries strideA words apart
+ *   out[b, m, n] = fp16( acc * fp32( alpha * (s_a * s_b) ) )   as bwta_matmul_tt
+ * B is `preparedB`: what bwta_prepare_act wrote for the fp16 matrix [batch * N, K] that stacks the
+ * batch entries' N rows (for Att V: V transposed, [heads * D, S]).  The boolean plane then plays the
+ * part the packed weights play in bwta_gemm_prepared, which is several times cheaper per product
+ * than expanding both operands from planes (bwta_matmul_tt).  Same bits as bwta_matmul_tt.
+ * Needs N a multiple of 128, the FP4 path (AUTO or BWTA_PATH_FP4, unchanged since the prepare
+ * call) and batch * N > 128; BWTA_ERR_UNSUPPORTED otherwise.  out fp16 [batch][M][ldo], ldo >= N,
+ * entries stride_out elements apart; s_a [batch, M] / s_b [batch, N] when VECTOR.
+ */
+int bwta_matmul_bool_prepared(const uint32_t *maskA, int64_t strideA, const void *preparedB,
+                              size_t preparedB_bytes, int batch, int M, int N, int K, const void *s_a,
+                              int a_scale_mode, const void *s_b, int b_scale_mode, float alpha,
+                              void *out, int64_t ldo, int64_t stride_out, bwta_stream_t stream);
+
+/*
  * Binary weights from full-precision ones (the paper's W_sign equation), per output channel n:
  *   mu_n = mean_k W[n, k];  wsign bit = 1 iff W[n, k] - mu_n < 0;  s_w[n] = fp16( mean_k |W[n, k] - mu_n| )
  * W is fp16 [N, ldw]; wsign is written in the layout of bwta_pack_weights; s_w is fp16 [N] (the

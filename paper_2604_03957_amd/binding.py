@@ -25,7 +25,7 @@ EXPORTS = ["bwta_plane_row_words", "bwta_workspace_bytes", "bwta_quantize_pack_a
            "bwta_set_path", "bwta_get_path", "bwta_auto_path", "bwta_version", "bwta_set_tile",
            "bwta_prepared_bytes", "bwta_prepare_act", "bwta_gemm_prepared", "bwta_gemm_grouped",
            "bwta_quantize_pack_bool", "bwta_matmul_tt", "bwta_prepare_weights", "bwta_act_scale",
-           "bwta_prepare_act_autoscale"]
+           "bwta_prepare_act_autoscale", "bwta_matmul_bool_prepared"]
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -76,6 +76,9 @@ _lib.bwta_prepare_weights.argtypes = [_P, _c.c_int64, _c.c_int, _c.c_int, _P, _P
 _lib.bwta_act_scale.restype = _c.c_int
 _lib.bwta_act_scale.argtypes = [_P, _c.c_int64, _c.c_int, _c.c_int, _P, _P]
 _lib.bwta_prepare_act_autoscale.restype = _c.c_int
+_lib.bwta_matmul_bool_prepared.restype = _c.c_int
+_lib.bwta_matmul_bool_prepared.argtypes = [_P, _c.c_int64, _P, _c.c_size_t, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _P, _c.c_int,
+                                           _P, _c.c_int, _c.c_float, _P, _c.c_int64, _c.c_int64, _P]
 _lib.bwta_prepare_act_autoscale.argtypes = [_P, _c.c_int64, _c.c_int, _c.c_int, _P, _P, _c.c_size_t, _P]
 _lib.bwta_strerror.restype = _c.c_char_p
 _lib.bwta_strerror.argtypes = [_c.c_int]
@@ -254,6 +257,18 @@ def bwta_prepare_act_autoscale(A, s_a, prepared, *, M, K, lda=None, prepared_byt
     lda = K if lda is None else lda
     _check(_lib.bwta_prepare_act_autoscale(_ptr(A), lda, M, K, _ptr(s_a), _ptr(prepared),
                                            _nbytes(prepared, prepared_bytes), _stream(stream)))
+
+
+def bwta_matmul_bool_prepared(maskA, preparedB, s_a, s_b, out, *, batch, M, N, K, alpha=1.0, strideA=None, ldo=None,
+                              stride_out=None, a_scale_mode=None, b_scale_mode=None, prepared_bytes=None, stream=None):
+    rw = plane_row_words(K)
+    strideA = M * rw if strideA is None else strideA
+    ldo = N if ldo is None else ldo
+    stride_out = M * ldo if stride_out is None else stride_out
+    _check(_lib.bwta_matmul_bool_prepared(_ptr(maskA), strideA, _ptr(preparedB), _nbytes(preparedB, prepared_bytes),
+                                          batch, M, N, K, _ptr(s_a), _mode(s_a, a_scale_mode), _ptr(s_b),
+                                          _mode(s_b, b_scale_mode), float(alpha), _ptr(out), ldo, stride_out,
+                                          _stream(stream)))
 
 
 def bwta_gemm_prepared(prepared, wsign, s_a, s_w, acc, out, *, M, N, K, ldo=None, a_scale_mode=None,

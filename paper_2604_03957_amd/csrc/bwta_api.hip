@@ -332,6 +332,40 @@ int bwta_matmul_tt(const uint32_t *maskA, const uint32_t *signA, int64_t strideA
     return hip_result(bwta::launch_matmul_tt(g, popcount_kernel, (hipStream_t)stream));
 }
 
+int bwta_matmul_bool_prepared(const uint32_t *maskA, int64_t strideA, const void *preparedB, size_t preparedB_bytes,
+                              int batch, int M, int N, int K, const void *s_a, int a_scale_mode, const void *s_b,
+                              int b_scale_mode, float alpha, void *out, int64_t ldo, int64_t stride_out,
+                              bwta_stream_t stream)
+{
+    int rc = check_gemm_common(M, N, K, s_a, a_scale_mode, s_b, b_scale_mode, out, ldo);
+    if (rc != BWTA_OK) return rc;
+    if (batch < 0) return BWTA_ERR_SHAPE;
+    if (batch == 0 || M == 0 || N == 0) return BWTA_OK;
+    if (batch > 65535) return BWTA_ERR_UNSUPPORTED;  // grid.y
+    if (!(alpha == alpha) || alpha - alpha != 0.0f) return BWTA_ERR_UNSUPPORTED;  // NaN / Inf
+    if (!maskA || !out) return BWTA_ERR_NULL;
+    // a workgroup's tile takes 128 rows of B: batch entries must not share one.  The prepared operand
+    // must hold matrix-core fragments, which bwta_prepare_act writes on the FP4 path above 128 rows.
+    if ((N & 127) != 0 || (int64_t)batch * N > 0x7fffffff) return BWTA_ERR_UNSUPPORTED;
+    const int rows_b = batch * N;
+    if (!fp4_uses_fragments(rows_b, K)) return BWTA_ERR_UNSUPPORTED;
+    const int64_t rw = bwta_plane_row_words(K);
+    if (batch > 1 && strideA < (int64_t)M * rw) return BWTA_ERR_SHAPE;
+    if (batch > 1 && stride_out < (int64_t)(M - 1) * ldo + N) return BWTA_ERR_SHAPE;
+    if (strideA & 3) return BWTA_ERR_ALIGN;  // batches keep the 16-byte alignment
+    if (!aligned(maskA, 16)) return BWTA_ERR_ALIGN;
+    if (!preparedB || preparedB_bytes < bwta_prepared_bytes(rows_b, K)) return BWTA_ERR_WORKSPACE;
+    if (!aligned(preparedB, 256)) return BWTA_ERR_ALIGN;
+    const uint32_t *frag = (const uint32_t *)((const char *)preparedB + 2 * plane_bytes(rows_b, K));
+    // in the tiled kernel's terms the fragment operand (B, N rows) is the "activation" side and the
+    // boolean plane (A, M rows) the 1-bit "weight" side; its epilogue writes out[m][n]
+    bwta::GemmArgs g{nullptr, nullptr, maskA, N, M, K, (int)rw,
+                     {(const uint16_t *)s_b, s_b ? b_scale_mode : BWTA_SCALE_NONE},
+                     {(const uint16_t *)s_a, s_a ? a_scale_mode : BWTA_SCALE_NONE},
+                     nullptr, (uint16_t *)out, ldo};
+    return hip_result(bwta::launch_att_v_fp4(g, frag, batch, strideA, stride_out, alpha, (hipStream_t)stream));
+}
+
 int bwta_prepare_weights(const void *W, int64_t ldw, int N, int K, uint32_t *wsign, void *s_w,
                          bwta_stream_t stream)
 {

@@ -62,6 +62,8 @@ void set_fp4_tile(int t);
 bool linear_fused_supported(const void *A, int64_t lda, const GemmArgs &g);
 hipError_t launch_linear_fused(const void *A, int64_t lda, const GemmArgs &g, hipStream_t st);
 void set_linear_fused(int mode, int r);
+hipError_t launch_att_v_fp4(const GemmArgs &g, const uint32_t *frag, int batch, int64_t w_stride_words,
+                            int64_t out_stride, float alpha, hipStream_t st);
 void set_gemv_tile(int g, int nch);
 hipError_t launch_gemm_fp4(const GemmArgs &g, uint32_t *frag, bool frag_ready, hipStream_t st);
 hipError_t launch_quantize_to_fp4(const void *A, int64_t lda, ScaleArg s_a, int M, int K, uint32_t *frag,

@@ -195,9 +195,11 @@ __device__ __forceinline__ void tile_of_workgroup(int tiles_n, int tiles_total, 
 // regrouped through the wavefront's LDS strip into 16-byte row-contiguous stores.  Lane (r32, h)
 // of block (j, i) holds token 32 i + r32 and channels 32 j + 8 g + 4 h + q (register 4 g + q).
 // sa_w / sw_w: this wavefront's token and channel scales in LDS.
-template <int WM, int WN>
+// ALPHA: the scale is fp32(alpha * (s_a * s_w)) (the attention MatMuls' prefix), else s_a * s_w (exact).
+template <int WM, int WN, bool ALPHA = false>
 __device__ __forceinline__ void store_tile_fp16(const v16f (&acc)[WN][WM], const GemmArgs &g, const float *sa_w,
-                                                const float *sw_w, uint16_t *strip, int m_wave, int n_wave, int lane)
+                                                const float *sw_w, uint16_t *strip, int m_wave, int n_wave, int lane,
+                                                float alpha = 1.0f)
 {
     const int r32 = lane & 31, h = lane >> 5;
     constexpr int PITCH = 32 * WN + 8;  // halfs; 16-byte aligned rows, conflict-free 8-byte writes
@@ -216,8 +218,10 @@ __device__ __forceinline__ void store_tile_fp16(const v16f (&acc)[WN][WM], const
                 const int nl = 32 * j + 8 * gq + 4 * h;
                 const float4 sw = *(const float4 *)(sw_w + nl);
                 uint2 hv;  // four consecutive channels of this token, exactly rounded
-                hv.x = scaled_to_half2(acc[j][i][4 * gq], sa * sw.x, acc[j][i][4 * gq + 1], sa * sw.y);
-                hv.y = scaled_to_half2(acc[j][i][4 * gq + 2], sa * sw.z, acc[j][i][4 * gq + 3], sa * sw.w);
+                float f0 = sa * sw.x, f1 = sa * sw.y, f2 = sa * sw.z, f3 = sa * sw.w;
+                if (ALPHA) f0 *= alpha, f1 *= alpha, f2 *= alpha, f3 *= alpha;
+                hv.x = scaled_to_half2(acc[j][i][4 * gq], f0, acc[j][i][4 * gq + 1], f1);
+                hv.y = scaled_to_half2(acc[j][i][4 * gq + 2], f2, acc[j][i][4 * gq + 3], f3);
                 *(uint2 *)(strip + r32 * PITCH + nl) = hv;
             }
         }
@@ -246,6 +250,25 @@ __device__ __forceinline__ void store_tile_fp16(const v16f (&acc)[WN][WM], const
     }
 }
 
+// bits of a boolean operand -> E2M1 nibbles (1 = 0b0010 = +1, 0 = 0b0000), same element order
+__device__ __forceinline__ v8i widen_bool(uint32_t x, uint32_t c22)
+{
+    v8i r;
+    r[0] = (int)((x << 1) & c22);
+    r[1] = (int)(x & c22);
+    r[2] = (int)((x >> 1) & c22);
+    r[3] = (int)((x >> 2) & c22);
+    r[4] = r[5] = r[6] = r[7] = 0;
+    return r;
+}
+
+// MODE 1 of k_gemm_fp4 (the BWTA_Att product: boolean attention plane x prepared ternary V^T, one
+// batch entry per blockIdx.y): where batch b's operands and output start, and the scale prefix
+struct BatchArgs {
+    int64_t frag_stride_dw, w_stride_words, out_stride;
+    float alpha;
+};
+
 constexpr int WD_PITCH = 20;  // dwords per LDS weight row: 16 words (512 k) + 4 pad
 
 // KS > 1: the K loop is split over KS groups of wavefronts inside the workgroup (each group owns
@@ -271,11 +294,26 @@ struct Cfg {
     static_assert(BN <= THREADS && BM <= THREADS, "one thread per scale");
 };
 
-template <int WM, int WN, int WAVES_M, int WAVES_N, int OCC, bool WITH_ACC, int KS, int D>
+// MODE 0: the linear layer.  MODE 1: the BWTA_Att product of the attention block, batched over
+// heads on blockIdx.y.  The 1-bit operand ("weights": N rows) is the boolean attention plane, whose
+// set bits count +1 and clear bits 0; the fragment operand ("activations": M rows) is V^T prepared
+// like an activation; the MFMA operands swap places, so a lane ends up with 4 consecutive rows of
+// V^T (head-dimension entries) for one attention row and the epilogue writes out[n][m], the
+// context matrix, with the scale fp32(alpha * (s_a * s_w)).
+template <int WM, int WN, int WAVES_M, int WAVES_N, int OCC, bool WITH_ACC, int KS, int D, int MODE>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KS) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
-void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, int tiles_n, int tiles_total)
+void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, int tiles_n, int tiles_total, BatchArgs ba)
 {
     using C = Cfg<WM, WN, WAVES_M, WAVES_N, KS>;
+    static_assert(MODE == 0 || (WM == WN && KS == 1 && !WITH_ACC), "the swapped epilogue reuses the strips as they are");
+    if constexpr (MODE == 1) {
+        const int64_t bz = blockIdx.y;
+        frag += bz * ba.frag_stride_dw;
+        g.wsign += bz * ba.w_stride_words;
+        g.out += bz * ba.out_stride;
+        if (g.s_a.mode == 2 && g.s_a.ptr) g.s_a.ptr += bz * g.M;
+        if (g.s_w.mode == 2 && g.s_w.ptr) g.s_w.ptr += bz * g.N;
+    }
     static_assert(D == 8 || D == 16, "activation prefetch distance in k steps: one or two slabs");
     extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
 
@@ -410,13 +448,18 @@ void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, int ti
 #pragma unroll
             for (int j = 0; j < WN; ++j) {
                 const uint4 x = xw[sub][j];
-                b[j] = widen_w(s == 0 ? x.x : s == 1 ? x.y : s == 2 ? x.z : x.w, m88, c22);
+                const uint32_t wbits = s == 0 ? x.x : s == 1 ? x.y : s == 2 ? x.z : x.w;
+                if constexpr (MODE == 1) b[j] = widen_bool(wbits, c22);
+                else b[j] = widen_w(wbits, m88, c22);
             }
 #pragma unroll
             for (int j = 0; j < WN; ++j)
 #pragma unroll
                 for (int i = 0; i < WM; ++i)
-                    acc[j][i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b[j], a[i], acc[j][i], 4, 4, 0, 0, 0, 0);
+                    if constexpr (MODE == 1)
+                        acc[j][i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i], b[j], acc[j][i], 4, 4, 0, 0, 0, 0);
+                    else
+                        acc[j][i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b[j], a[i], acc[j][i], 4, 4, 0, 0, 0, 0);
             if (!HALF) load_a(ring[slot], 8 * (pr + KS * (D / 8)) + s8);  // refill the slot D steps of this group ahead
         }
         }
@@ -493,16 +536,32 @@ void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, int ti
     // the loop's last barrier retired every read of the weight slabs, whose LDS the strips reuse
     uint16_t *strip = (uint16_t *)(smem + C::BN) + wl * C::STRIP_HALFS;
     if (kg != 0) return;  // no barrier below this point
-    store_tile_fp16<WM, WN>(acc, g, sa_lds + wm * WM * 32, sw_lds + wn * WN * 32, strip, m_wave, n_wave, lane);
+    if constexpr (MODE == 1) {
+        // lane (r32, h) of block (j, i) holds attention row 32 j + r32 and V^T rows 32 i + 8 g + 4 h + q:
+        // the same epilogue with the two sides exchanged
+        v16f acct[WM][WN];
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+#pragma unroll
+            for (int i = 0; i < WM; ++i) acct[i][j] = acc[j][i];
+        GemmArgs gs = g;
+        gs.M = g.N;
+        gs.N = g.M;
+        store_tile_fp16<WN, WM, true>(acct, gs, sw_lds + wn * WN * 32, sa_lds + wm * WM * 32, strip, n_wave, m_wave, lane,
+                                      ba.alpha);
+    } else {
+        store_tile_fp16<WM, WN>(acc, g, sa_lds + wm * WM * 32, sw_lds + wn * WN * 32, strip, m_wave, n_wave, lane);
+    }
 }
 
-template <int WM, int WN, int WAVES_M, int WAVES_N, int OCC, bool WITH_ACC, int KS = 1, int D = 8>
-hipError_t launch(const GemmArgs &g, const uint32_t *frag, int s_pad, hipStream_t st)
+template <int WM, int WN, int WAVES_M, int WAVES_N, int OCC, bool WITH_ACC, int KS = 1, int D = 8, int MODE = 0>
+hipError_t launch(const GemmArgs &g, const uint32_t *frag, int s_pad, hipStream_t st, int batch = 1,
+                  BatchArgs ba = BatchArgs{0, 0, 0, 1.0f})
 {
     using C = Cfg<WM, WN, WAVES_M, WAVES_N, KS>;
     static bool configured = false;  // benign race: setting the attribute twice is harmless
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_gemm_fp4<WM, WN, WAVES_M, WAVES_N, OCC, WITH_ACC, KS, D>,
+        hipError_t e = hipFuncSetAttribute((const void *)k_gemm_fp4<WM, WN, WAVES_M, WAVES_N, OCC, WITH_ACC, KS, D, MODE>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM_BYTES);
         if (e != hipSuccess) return e;
         configured = true;
@@ -510,8 +569,8 @@ hipError_t launch(const GemmArgs &g, const uint32_t *frag, int s_pad, hipStream_
     const int tiles_n = (g.N + C::BN - 1) / C::BN, tiles_m = (g.M + C::BM - 1) / C::BM;
     const int64_t total = (int64_t)tiles_n * tiles_m;
     if (total > 0x7fffffff) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((k_gemm_fp4<WM, WN, WAVES_M, WAVES_N, OCC, WITH_ACC, KS, D>), dim3((unsigned)total), dim3(C::THREADS),
-                       C::SMEM_BYTES, st, g, frag, s_pad, tiles_n, (int)total);
+    hipLaunchKernelGGL((k_gemm_fp4<WM, WN, WAVES_M, WAVES_N, OCC, WITH_ACC, KS, D, MODE>), dim3((unsigned)total, batch),
+                       dim3(C::THREADS), C::SMEM_BYTES, st, g, frag, s_pad, tiles_n, (int)total, ba);
     return hipGetLastError();
 }
 
@@ -732,6 +791,17 @@ void set_linear_fused(int mode, int r)
 {
     g_linear_fused = mode;
     g_linear_fused_r = r;
+}
+
+// BWTA_Att with V^T prepared as fragments.  g: M = rows of V^T per batch entry (a multiple of 128),
+// N = attention rows per entry, wsign = the boolean plane, s_a / s_w = the scales of V^T / of the
+// attention operand, out = the context matrix [batch][N][ldo].
+hipError_t launch_att_v_fp4(const GemmArgs &g, const uint32_t *frag, int batch, int64_t w_stride_words,
+                            int64_t out_stride, float alpha, hipStream_t st)
+{
+    const int s_pad = fp4_s_pad(g.rw);
+    const BatchArgs ba{(int64_t)(g.M / 32) * s_pad * 256, w_stride_words, out_stride, alpha};
+    return launch<2, 2, 2, 2, 2, false, 1, 8, 1>(g, frag, s_pad, st, batch, ba);
 }
 
 static int g_fp4_tile = 0;

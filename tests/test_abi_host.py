@@ -159,3 +159,21 @@ def test_weight_preparation_entry_points_reject_bad_arguments():
     assert _code(au, FAKE, FAKE, None, **kw) == B.ERR_WORKSPACE
     assert _code(au, FAKE, FAKE, FAKE, **dict(kw, K=40000, prepared_bytes=1 << 30)) == B.ERR_UNSUPPORTED
     au(FAKE, FAKE, FAKE, **dict(kw, M=0))
+
+
+def test_prepared_attention_product_rejects_bad_arguments():
+    f = B.bwta_matmul_bool_prepared
+    kw = dict(batch=2, M=64, N=128, K=256, stream=0, prepared_bytes=B.prepared_bytes(256, 256))
+    assert _code(f, None, FAKE, None, None, FAKE, **kw) == B.ERR_NULL
+    assert _code(f, FAKE, FAKE, None, None, None, **kw) == B.ERR_NULL
+    assert _code(f, FAKE, None, None, None, FAKE, **kw) == B.ERR_WORKSPACE
+    assert _code(f, FAKE, FAKE, None, None, FAKE, **dict(kw, prepared_bytes=64)) == B.ERR_WORKSPACE
+    assert _code(f, FAKE, FAKE + 16, None, None, FAKE, **kw) == B.ERR_ALIGN
+    assert _code(f, FAKE + 4, FAKE, None, None, FAKE, **kw) == B.ERR_ALIGN
+    assert _code(f, FAKE, FAKE, None, None, FAKE, **dict(kw, strideA=64 * 8 + 2)) == B.ERR_ALIGN
+    assert _code(f, FAKE, FAKE, None, None, FAKE, **dict(kw, N=96)) == B.ERR_UNSUPPORTED      # not a multiple of 128
+    assert _code(f, FAKE, FAKE, None, None, FAKE, **dict(kw, batch=1)) == B.ERR_UNSUPPORTED   # 128 rows: no fragments
+    assert _code(f, FAKE, FAKE, None, None, FAKE, **dict(kw, alpha=float("nan"))) == B.ERR_UNSUPPORTED
+    assert _code(f, FAKE, FAKE, None, None, FAKE, **dict(kw, ldo=64)) == B.ERR_SHAPE
+    assert _code(f, FAKE, FAKE, None, None, FAKE, **dict(kw, strideA=8)) == B.ERR_SHAPE
+    f(FAKE, FAKE, None, None, FAKE, **dict(kw, batch=0))

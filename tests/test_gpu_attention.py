@@ -190,3 +190,41 @@ def test_empty_inputs_are_noops():
     B.bwta_matmul_tt(z, z, z, z, None, None, z, None, batch=1, M=0, N=4, K=32)
     B.bwta_quantize_pack_bool(z, None, z, M=0, K=32)
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("batch,M,N,K,vec", [(2, 200, 128, 300, False), (3, 257, 256, 1000, True), (1, 64, 256, 128, False),
+                                             (2, 130, 128, 2048, True)])
+def test_att_v_with_v_prepared_once(batch, M, N, K, vec):
+    """BWTA_Att through bwta_matmul_bool_prepared: the boolean plane against V^T prepared like an
+    activation (bwta_prepare_act).  Ragged attention rows, K tails, vector and scalar scales, a scale
+    prefix, padded strides; nothing is written between rows or batch entries."""
+    _say("att prepared", batch, M, N, K, vec)
+    att, vt = _operands(900 + M, batch, M, N, K, a_bool=True, p0a=0.8)
+    rw = B.plane_row_words(K)
+    pad_a, ldo, pad_out = 8, N + 8, 24
+    ma = np.zeros((batch, M * rw + pad_a), np.uint32)
+    for i in range(batch):
+        ma[i, :M * rw] = oracle.pack_act(att[i])[0].reshape(-1)
+    s_a = synth.scales(900, 1, batch * M) if vec else synth.scales(900, 1, 1)
+    s_b = synth.scales(900, 2, batch * N) if vec else None
+    alpha = 0.37
+    v16 = np.ascontiguousarray(vt.reshape(batch * N, K).astype(np.float16))     # +-1 and 0: ternarised as they are
+    prep = torch.empty(B.prepared_bytes(batch * N, K), dtype=torch.uint8, device=DEV)
+    stride_out = M * ldo + pad_out
+    out = torch.full((batch * stride_out,), float("nan"), dtype=torch.float16, device=DEV)
+    B.bwta_prepare_act(dev(v16), None, prep, M=batch * N, K=K)
+    B.bwta_matmul_bool_prepared(dev(ma), prep, dev(s_a), dev(s_b), out, batch=batch, M=M, N=N, K=K, alpha=alpha,
+                                strideA=M * rw + pad_a, ldo=ldo, stride_out=stride_out)
+    torch.cuda.synchronize()
+    out = out.cpu().numpy()
+    for i in range(batch):
+        want_acc = oracle.gemm_unpacked(att[i], vt[i])
+        sai = s_a if s_a.size == 1 else s_a.reshape(batch, M)[i]
+        sbi = None if s_b is None else s_b.reshape(batch, N)[i]
+        want = oracle.epilogue_alpha(want_acc, sai, sbi, alpha)
+        got = np.stack([out[i * stride_out + m * ldo: i * stride_out + m * ldo + N] for m in range(M)])
+        assert max_rel_err(got, want) <= RTOL
+        assert same_half(got, want)
+        gap = np.stack([out[i * stride_out + m * ldo + N: i * stride_out + (m + 1) * ldo] for m in range(M - 1)])
+        assert np.isnan(gap).all()
+        assert np.isnan(out[i * stride_out + M * ldo - (ldo - N): (i + 1) * stride_out]).all()
