@@ -341,7 +341,7 @@ int bwta_matmul_bool_prepared(const uint32_t *maskA, int64_t strideA, const void
     if (rc != BWTA_OK) return rc;
     if (batch < 0) return BWTA_ERR_SHAPE;
     if (batch == 0 || M == 0 || N == 0) return BWTA_OK;
-    if (batch > 65535) return BWTA_ERR_UNSUPPORTED;  // grid.y
+    if (batch > 65535) return BWTA_ERR_UNSUPPORTED;  // same limit as bwta_matmul_tt
     if (!(alpha == alpha) || alpha - alpha != 0.0f) return BWTA_ERR_UNSUPPORTED;  // NaN / Inf
     if (!maskA || !out) return BWTA_ERR_NULL;
     // a workgroup's tile takes 128 rows of B: batch entries must not share one.  The prepared operand

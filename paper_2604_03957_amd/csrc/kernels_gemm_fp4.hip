@@ -267,6 +267,7 @@ __device__ __forceinline__ v8i widen_bool(uint32_t x, uint32_t c22)
 struct BatchArgs {
     int64_t frag_stride_dw, w_stride_words, out_stride;
     float alpha;
+    int batch;
 };
 
 constexpr int WD_PITCH = 20;  // dwords per LDS weight row: 16 words (512 k) + 4 pad
@@ -295,7 +296,7 @@ struct Cfg {
 };
 
 // MODE 0: the linear layer.  MODE 1: the BWTA_Att product of the attention block, batched over
-// heads on blockIdx.y.  The 1-bit operand ("weights": N rows) is the boolean attention plane, whose
+// heads (a group of workgroups per head).  The 1-bit operand ("weights": N rows) is the boolean attention plane, whose
 // set bits count +1 and clear bits 0; the fragment operand ("activations": M rows) is V^T prepared
 // like an activation; the MFMA operands swap places, so a lane ends up with 4 consecutive rows of
 // V^T (head-dimension entries) for one attention row and the epilogue writes out[n][m], the
@@ -306,8 +307,25 @@ void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, int ti
 {
     using C = Cfg<WM, WN, WAVES_M, WAVES_N, KS>;
     static_assert(MODE == 0 || (WM == WN && KS == 1 && !WITH_ACC), "the swapped epilogue reuses the strips as they are");
+    int tm, tn;
     if constexpr (MODE == 1) {
-        const int64_t bz = blockIdx.y;
+        // One batch entry (head) per group of tiles_total workgroups.  With a multiple of 8 entries
+        // the groups are dealt to the XCDs whole (the hardware sends consecutive workgroup ids to the 8
+        // XCDs in turn): all tiles of a head then share one L2, which fetches that head's V^T
+        // fragments once instead of once per XCD.
+        int64_t bz;
+        if ((ba.batch & 7) == 0) {
+            const int L = blockIdx.x, k = L >> 3;
+            bz = (L & 7) + 8 * (k / tiles_total);
+            const int t = k % tiles_total;
+            tm = t % (tiles_total / tiles_n);
+            tn = t / (tiles_total / tiles_n);
+        } else {
+            bz = blockIdx.x / tiles_total;
+            const int t = blockIdx.x % tiles_total;
+            tm = t % (tiles_total / tiles_n);
+            tn = t / (tiles_total / tiles_n);
+        }
         frag += bz * ba.frag_stride_dw;
         g.wsign += bz * ba.w_stride_words;
         g.out += bz * ba.out_stride;
@@ -317,8 +335,7 @@ void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, int ti
     static_assert(D == 8 || D == 16, "activation prefetch distance in k steps: one or two slabs");
     extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
 
-    int tm, tn;
-    tile_of_workgroup(tiles_n, tiles_total, tm, tn);
+    if constexpr (MODE == 0) tile_of_workgroup(tiles_n, tiles_total, tm, tn);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int kg = KS == 1 ? 0 : wave / C::GROUP_WAVES;  // k group
@@ -556,7 +573,7 @@ void k_gemm_fp4(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, int ti
 
 template <int WM, int WN, int WAVES_M, int WAVES_N, int OCC, bool WITH_ACC, int KS = 1, int D = 8, int MODE = 0>
 hipError_t launch(const GemmArgs &g, const uint32_t *frag, int s_pad, hipStream_t st, int batch = 1,
-                  BatchArgs ba = BatchArgs{0, 0, 0, 1.0f})
+                  BatchArgs ba = BatchArgs{0, 0, 0, 1.0f, 1})
 {
     using C = Cfg<WM, WN, WAVES_M, WAVES_N, KS>;
     static bool configured = false;  // benign race: setting the attribute twice is harmless
@@ -569,7 +586,8 @@ hipError_t launch(const GemmArgs &g, const uint32_t *frag, int s_pad, hipStream_
     const int tiles_n = (g.N + C::BN - 1) / C::BN, tiles_m = (g.M + C::BM - 1) / C::BM;
     const int64_t total = (int64_t)tiles_n * tiles_m;
     if (total > 0x7fffffff) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((k_gemm_fp4<WM, WN, WAVES_M, WAVES_N, OCC, WITH_ACC, KS, D, MODE>), dim3((unsigned)total, batch),
+    if (total * batch > 0x7fffffff) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((k_gemm_fp4<WM, WN, WAVES_M, WAVES_N, OCC, WITH_ACC, KS, D, MODE>), dim3((unsigned)(total * batch)),
                        dim3(C::THREADS), C::SMEM_BYTES, st, g, frag, s_pad, tiles_n, (int)total, ba);
     return hipGetLastError();
 }
@@ -800,7 +818,7 @@ hipError_t launch_att_v_fp4(const GemmArgs &g, const uint32_t *frag, int batch, 
                             int64_t out_stride, float alpha, hipStream_t st)
 {
     const int s_pad = fp4_s_pad(g.rw);
-    const BatchArgs ba{(int64_t)(g.M / 32) * s_pad * 256, w_stride_words, out_stride, alpha};
+    const BatchArgs ba{(int64_t)(g.M / 32) * s_pad * 256, w_stride_words, out_stride, alpha, batch};
     return launch<2, 2, 2, 2, 2, false, 1, 8, 1>(g, frag, s_pad, st, batch, ba);
 }
 

@@ -193,11 +193,12 @@ def test_empty_inputs_are_noops():
 
 
 @pytest.mark.parametrize("batch,M,N,K,vec", [(2, 200, 128, 300, False), (3, 257, 256, 1000, True), (1, 64, 256, 128, False),
-                                             (2, 130, 128, 2048, True)])
+                                             (2, 130, 128, 2048, True), (8, 300, 128, 200, True), (16, 33, 256, 64, False)])
 def test_att_v_with_v_prepared_once(batch, M, N, K, vec):
     """BWTA_Att through bwta_matmul_bool_prepared: the boolean plane against V^T prepared like an
     activation (bwta_prepare_act).  Ragged attention rows, K tails, vector and scalar scales, a scale
-    prefix, padded strides; nothing is written between rows or batch entries."""
+    prefix, padded strides; nothing is written between rows or batch entries.  Batch counts that are
+    and are not multiples of 8 (the two workgroup-to-head mappings)."""
     _say("att prepared", batch, M, N, K, vec)
     att, vt = _operands(900 + M, batch, M, N, K, a_bool=True, p0a=0.8)
     rw = B.plane_row_words(K)
