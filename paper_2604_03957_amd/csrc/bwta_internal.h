@@ -95,30 +95,71 @@ __device__ __forceinline__ void word_slot(int q, int &step, int &half)
     half = (j & 3) >> 1;
 }
 
+// ---- ternarisation of binary16 values in packed half precision ---------------------------------
+//
+// For binary16 x and T > 0 the sums x - pred(T) and -x - T (pred = next value below) are rounded
+// once, and a rounded difference of two binary16 values has the sign of the exact one and is zero
+// only when they are equal (gradual underflow).  With the result clamped to [0, 1] (NaN clamps to
+// 0):   clamp(x - pred(T)) != 0  <=>  x >= T,      clamp(-x - T) != 0  <=>  x < -T,
+// which is the paper's threshold rule with T = s / 2, ties and all, at one instruction per two
+// elements and side.  T = s / 2 is a binary16 value unless s lies below 2^-13 with an odd last
+// bit; such rows compare 2 x (exact, or +-Inf on the correct side) against s instead.
+struct TernaryThr {
+    uint32_t cp, cn;  // -pred(T) and -T, each in both halves
+    bool twice;       // compare 2 x against T = s
+};
+
+__device__ __forceinline__ TernaryThr ternary_thresholds(uint32_t s_bits, bool row_valid)
+{
+    const bool ok = row_valid && s_bits > 0 && s_bits < 0x7c00;  // finite and > 0; anything else: all zero
+    const bool halves = s_bits >= 0x0800 || (s_bits & 1) == 0;
+    const uint32_t T = s_bits >= 0x0800 ? s_bits - 0x0400 : (halves ? s_bits >> 1 : s_bits);
+    const uint32_t Tp = T - 1;
+    uint32_t cp = Tp ? (0x8000u | Tp) : 0u;  // +0, not -0, for pred(T) = 0: (-0) + (+0) is +0
+    uint32_t cn = 0x8000u | T;
+    if (!ok) cp = cn = 0xfc00u;  // -Inf: every sum is -Inf or NaN
+    TernaryThr t;
+    t.cp = cp * 0x10001u;
+    t.cn = cn * 0x10001u;
+    t.twice = ok && !halves;
+    return t;
+}
+
 // 8 fp16 values of one row (lane j of a quad holds elements 8 j .. 8 j + 7 of a 32-element word) ->
 // the dword this lane contributes to the word's fragment: nibble i of dword d holds element
-// 4 i + d (bit 1 = non-zero, bit 3 = negative).  Compares are exact in fp32; NaN thresholds (invalid
-// scale) and NaN values fail both.
-__device__ __forceinline__ uint32_t fragment_dword(const uint4 &x, float hthr, float nthr, int j)
+// 4 i + d (bit 1 = non-zero, bit 3 = negative).
+__device__ __forceinline__ uint32_t fragment_dword(const uint4 &x, const TernaryThr &t, int j)
 {
-    const uint32_t w[4] = {x.x, x.y, x.z, x.w};
-    uint32_t V = 0;  // byte d = nibbles of elements d (low) and d + 4 (high): mask -> bit 1, sign -> bit 3
+    uint32_t w[4] = {x.x, x.y, x.z, x.w};  // elements (0,1) (2,3) (4,5) (6,7)
+    if (t.twice) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const float a = half_bits_to_float((uint16_t)(w[e >> 1] >> (16 * (e & 1))));
-        uint32_t sel = a >= hthr ? 1u : 0u;  // mask bit; NaN fails both compares
-        sel = a < nthr ? 5u : sel;           // mask bit and, two places up, the sign bit
-        const int base = 8 * (e & 3) + 4 * (e >> 2);
-        V = (sel << (base + 1)) | V;
+        for (int d = 0; d < 4; ++d) asm("v_pk_add_f16 %0, %1, %1" : "=v"(w[d]) : "v"(w[d]));
     }
-    // quad byte transpose: lane d of the quad collects byte d of every lane -> dword d of the word
+    uint32_t one2 = 0x00010001u;
+    // byte 0 = elements 0 (low nibble) and 4 (high), byte 1 = 2 and 6, byte 2 = 1 and 5, byte 3 = 3 and 7
+    uint32_t V = 0;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        uint32_t p, n, gp, gn;
+        asm("v_pk_add_f16 %0, %1, %2 clamp" : "=v"(p) : "v"(w[d]), "v"(t.cp));
+        asm("v_pk_add_f16 %0, %1, %2 neg_lo:[1,0] neg_hi:[1,0] clamp" : "=v"(n) : "v"(w[d]), "v"(t.cn));
+        asm("v_pk_min_u16 %0, %1, %2" : "=v"(gp) : "v"(p), "v"(one2));  // 1 where x >= T
+        asm("v_pk_min_u16 %0, %1, %2" : "=v"(gn) : "v"(n), "v"(one2));  // 1 where x < -T
+        const uint32_t sel = __umul24(gn, 5u) + gp;  // per half: non-zero bit, and two places up the sign bit
+        const int sh = d == 0 ? 1 : d == 1 ? 9 : d == 2 ? 5 : 13;
+        V = (sel << sh) | V;
+    }
+    // quad byte transpose: lane d of the quad collects the byte holding elements d and d + 4 of
+    // every lane -> dword d of the word
     const uint32_t x0 = __builtin_amdgcn_mov_dpp(V, 0x00, 0xf, 0xf, true);  // quad_perm [0,0,0,0]
     const uint32_t x1 = __builtin_amdgcn_mov_dpp(V, 0x55, 0xf, 0xf, true);  // [1,1,1,1]
     const uint32_t x2 = __builtin_amdgcn_mov_dpp(V, 0xaa, 0xf, 0xf, true);  // [2,2,2,2]
     const uint32_t x3 = __builtin_amdgcn_mov_dpp(V, 0xff, 0xf, 0xf, true);  // [3,3,3,3]
-    const uint32_t sh = 8 * j;
-    return ((x0 >> sh) & 0xffu) | (((x1 >> sh) & 0xffu) << 8) | (((x2 >> sh) & 0xffu) << 16) |
-                       (((x3 >> sh) & 0xffu) << 24);
+    const uint32_t b = ((j & 1) << 1) | (j >> 1);                // the byte with elements j and j + 4
+    const uint32_t pick = 0x0c0c0000u | ((4u + b) << 8) | b;      // byte b of the second, then of the first source
+    const uint32_t lo = __builtin_amdgcn_perm(x1, x0, pick);     // [x0.b, x1.b, 0, 0]
+    const uint32_t hi = __builtin_amdgcn_perm(x3, x2, pick);
+    return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
 }
 
 __device__ __forceinline__ float load_scale(const ScaleArg &s, int row)

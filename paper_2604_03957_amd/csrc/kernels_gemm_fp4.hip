@@ -140,20 +140,14 @@ __global__ __launch_bounds__(256) void k_quantize_to_fp4(const uint16_t *__restr
         }
     }
 
-    // thresholds: 0.5 s is exact.  An invalid scale turns them into NaN, against which every compare
-    // fails; elements past K are loaded as +0 and fail both compares as well, so the element loop
-    // needs no validity logic: convert, two compares, two selects, one shift-or.
-    float hthr = __builtin_nanf("");
-    {
-        const float s = have_scale ? half_bits_to_float(s_bits) : 1.0f;
-        if (m < M && (s > 0.0f) && (s < __builtin_inff())) hthr = 0.5f * s;
-    }
-    const float nthr = -hthr;
+    // An invalid scale (and a row past M) ternarises to zero; elements past K are loaded as +0 and
+    // are zero under every valid threshold, so the element loop needs no validity logic.
+    const TernaryThr thr = ternary_thresholds(have_scale ? s_bits : 0x3c00u, m < M);
 
 #pragma unroll
     for (int it = 0; it < QF_R; ++it) {
         const int q = q0 + 2 * it;
-        const uint32_t D = fragment_dword(x[it], hthr, nthr, j);
+        const uint32_t D = fragment_dword(x[it], thr, j);
         int step, half;
         word_slot(q, step, half);
         if (step < s_pad) frag[(((int64_t)rb * s_pad + step) * 64 + half * 32 + row) * 4 + j] = D;
@@ -675,13 +669,8 @@ __global__ __launch_bounds__(256) void k_linear_fused(const uint16_t *__restrict
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- ternarise the strip into LDS
-    float hthr = __builtin_nanf("");
-    {
-        const float sc = have_sa ? half_bits_to_float(sa_bits) : 1.0f;
-        if (m < g.M && (sc > 0.0f) && (sc < __builtin_inff())) hthr = 0.5f * sc;
-        if ((quad >> 5) == 0 && j == 0) s_sa[row] = m < g.M ? sc : 0.0f;
-    }
-    const float nthr = -hthr;
+    const TernaryThr thr = ternary_thresholds(have_sa ? sa_bits : 0x3c00u, m < g.M);
+    if ((quad >> 5) == 0 && j == 0) s_sa[row] = m < g.M ? (have_sa ? half_bits_to_float(sa_bits) : 1.0f) : 0.0f;
 #pragma unroll
     for (int i = 0; i < SW_PER; ++i) {
         const int e = tid + 256 * i, n = 32 * cb0 + e;
@@ -692,7 +681,7 @@ __global__ __launch_bounds__(256) void k_linear_fused(const uint16_t *__restrict
         const int q = 2 * it + (quad >> 5), k0 = 32 * q + 8 * j;
         uint4 v = x[it];
         if (!(m < g.M && k0 < g.K)) v = make_uint4(0, 0, 0, 0);
-        const uint32_t D = fragment_dword(v, hthr, nthr, j);
+        const uint32_t D = fragment_dword(v, thr, j);
         const int jw = q & 7, step = 4 * (q >> 3) + (jw & 3), half = jw >> 2;
         sA[(step * 64 + half * 32 + row) * 4 + j] = D;
     }

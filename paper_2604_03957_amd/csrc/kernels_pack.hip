@@ -485,17 +485,16 @@ __global__ __launch_bounds__(NT) void k_act_scale_quantize(const uint16_t *__res
     const long long S = block_sum<NT>(double_units(part), s_ll);
     const uint16_t s_bits = double_to_half_bits((double)S / ((double)K * 8388608.0));  // 2 S / (K 2^24)
     if (threadIdx.x == 0 && m < M) s_out[m] = s_bits;
-    // thresholds +-0.5 s, exact in fp32; an all-zero (or all non-finite) row has s = 0, an invalid
-    // scale: NaN thresholds fail every compare and the row ternarises to zero
+    // an all-zero (or all non-finite) row has s = 0, an invalid scale: the row ternarises to zero
     const float sc = half_bits_to_float(s_bits);
     const bool ok = sc > 0.0f && sc < __builtin_inff();
-    const float hthr = ok ? 0.5f * sc : __builtin_nanf(""), nthr = -hthr;
+    const TernaryThr thr = ternary_thresholds(s_bits, true);
     const int lane = threadIdx.x & 63;
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
         const int c = (int)threadIdx.x + NT * g, q = c >> 2, j = c & 3;
         if (FRAG) {
-            const uint32_t D = fragment_dword(x[g], hthr, nthr, j);
+            const uint32_t D = fragment_dword(x[g], thr, j);
             int step, half;
             word_slot(q, step, half);
             if (step < s_pad)

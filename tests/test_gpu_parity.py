@@ -96,35 +96,40 @@ def test_quantize_pack_every_half_pattern():
 
 
 def test_fragment_routes_every_half_pattern():
-    """All 65 536 fp16 bit patterns through the two kernels that ternarise straight into matrix-core
-    fragments (bwta_prepare_act on the tiled path, and the one-launch linear), under seven scales
-    including a subnormal and the largest one.  The fragments are opaque, so the check is on what
-    they produce against 64 random weight rows: one wrong decision changes every accumulator of its
-    token by 1 or 2."""
+    """All 65 536 fp16 bit patterns, each under every one of 14 scales, through the two kernels that
+    ternarise straight into matrix-core fragments (bwta_prepare_act on the tiled path, and the
+    one-launch linear).  The scales include the smallest subnormal, odd and even subnormals, the
+    values around 2^-14 and 2^-13 (where half the scale stops being a binary16 value) and the largest
+    finite one.  The fragments are opaque, so the check is on what they produce against 64 random
+    weight rows: one wrong decision changes every accumulator of its token by 1 or 2."""
     M, K, N = 256, 256, 64
     A = np.arange(65536, dtype=np.uint32).astype(np.uint16).view(np.float16).reshape(M, K)
-    svals = np.array([1.0, 0.5, 1.5, 6e-8, 65504.0, 2.0 ** -14, 0.0999], np.float16)
-    s = svals[np.arange(M) % len(svals)]
+    svals = np.array([0x3c00, 0x3800, 0x3e00, 0x0001, 0x0002, 0x0003, 0x03ff, 0x0400, 0x0401, 0x07ff, 0x0800,
+                      0x0801, 0x7bff, 0x2e65], np.uint16).view(np.float16)
     w = synth.binary_pm1(35, 1, (N, K))
     ones = np.ones(N, np.float16)
-    _, want_acc, want_out = oracle.linear(A, s, w, ones)
     wsign = gpu_pack_weights(w)
+    wsign2 = gpu_pack_weights(np.concatenate([w, w], axis=0))  # the one-launch kernel wants at least 128 channels
+    prep = torch.empty(B.prepared_bytes(M, K), dtype=torch.uint8, device="cuda:0")
+    ws = torch.empty(B.workspace_bytes(M, 128, K), dtype=torch.uint8, device="cuda:0")
     B.set_path(B.PATH_FP4)
     try:
-        prep = torch.empty(B.prepared_bytes(M, K), dtype=torch.uint8, device="cuda:0")
-        acc = torch.full((M, N), 123456, dtype=torch.int32, device="cuda:0")
-        B.bwta_prepare_act(dev(A), dev(s), prep, M=M, K=K)
-        B.bwta_gemm_prepared(prep, wsign, dev(s), dev(ones), acc, None, M=M, N=N, K=K)
-        torch.cuda.synchronize()
-        assert np.array_equal(acc.cpu().numpy(), want_acc)
-        ws = torch.empty(B.workspace_bytes(M, 128, K), dtype=torch.uint8, device="cuda:0")
-        w2 = np.concatenate([w, w], axis=0)  # the one-launch kernel wants at least 128 channels
-        out = torch.full((M, 128), 7.0, dtype=torch.float16, device="cuda:0")
-        B.set_tile(901)
-        B.bwta_linear(dev(A), dev(s), gpu_pack_weights(w2), dev(np.ones(128, np.float16)), out, ws, M=M, N=128, K=K)
-        torch.cuda.synchronize()
-        got = out.cpu().numpy()
-        assert same_half(np.ascontiguousarray(got[:, :N]), want_out) and same_half(np.ascontiguousarray(got[:, N:]), want_out)
+        for rot in range(len(svals)):
+            s = svals[(np.arange(M) + rot) % len(svals)]
+            _, want_acc, want_out = oracle.linear(A, s, w, ones)
+            acc = torch.full((M, N), 123456, dtype=torch.int32, device="cuda:0")
+            B.set_tile(0)
+            B.bwta_prepare_act(dev(A), dev(s), prep, M=M, K=K)
+            B.bwta_gemm_prepared(prep, wsign, dev(s), dev(ones), acc, None, M=M, N=N, K=K)
+            torch.cuda.synchronize()
+            assert np.array_equal(acc.cpu().numpy(), want_acc), rot
+            out = torch.full((M, 128), 7.0, dtype=torch.float16, device="cuda:0")
+            B.set_tile(901)
+            B.bwta_linear(dev(A), dev(s), wsign2, dev(np.ones(128, np.float16)), out, ws, M=M, N=128, K=K)
+            torch.cuda.synchronize()
+            got = out.cpu().numpy()
+            assert same_half(np.ascontiguousarray(got[:, :N]), want_out), rot
+            assert same_half(np.ascontiguousarray(got[:, N:]), want_out), rot
     finally:
         B.set_tile(0)
         B.set_path(B.PATH_AUTO)
