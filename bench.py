@@ -217,30 +217,51 @@ def run_c2(args, torch, B, synth):
     ops = sum(L.ops for L in layers)
     value = ops / (ms_per_step * 1e-3) / 1e12
 
-    # per-kernel durations: HIP events on the launch stream.  The product is timed through its
-    # single-kernel entry point (a 10 us kernel keeps the GPU, not the host's launch rate, the
-    # bound); a loop over the 3-7 us ternarise kernel alone would time the host (about 8 us per
-    # call through Python), so its figure is the two-kernel bwta_linear minus the product.
-    kern = []
+    # per-kernel durations: HIP events on the launch stream.  A layer that bwta_linear runs as one
+    # kernel (short K) is timed as such, and its two-kernel form (tuning hook 900) beside it.  The
+    # product is timed through its single-kernel entry point (a 10 us kernel keeps the GPU, not the
+    # host's launch rate, the bound); a loop over the 3-7 us ternarise kernel alone would time the
+    # host (about 8 us per call through Python), so its figure is the two-kernel bwta_linear minus
+    # the product.
+    kern, contraction_ms = [], []
     for L, c in zip(layers, cfgs):
+        launches = B.linear_launches(L.M, L.N, L.K)
         tl = _event_ms(torch, lambda: L.linear(B), args.steps, args.warmup)
         tg = _event_ms(torch, lambda: L.gemm_prepared(B), args.steps, args.warmup)
-        tq = max(tl - tg, 1e-6)
-        kern.append({"layer": c["name"], "linear_us": round(tl * 1e3, 2), "ternarize_us": round(tq * 1e3, 2),
-                     "gemm_us": round(tg * 1e3, 2),
-                     "ternarize_GBs": round((L.M * L.K * 2.5 + 2 * L.M) / (tq * 1e-3) / 1e9, 1),
-                     "gemm_TOPS": round(L.ops / (tg * 1e-3) / 1e12, 2), "path": _kernel_path_name(B, L.M, L.N, L.K)})
-    avg_gemm_ms = sum(k["gemm_us"] for k in kern) / len(kern) / 1e3
-    achieved = (ops / len(layers)) / (avg_gemm_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "k_gemm_fp4 (FP4 MFMA product + scale epilogue), mean of the two layers",
+        k = {"layer": c["name"], "launches": launches, "linear_us": round(tl * 1e3, 2)}
+        t2 = tl
+        if launches == 1:
+            k["kernel"] = "k_linear_fused (ternarise + FP4 MFMA product + scale epilogue)"
+            B.set_tile(900)
+            try:
+                t2 = _event_ms(torch, lambda: L.linear(B), args.steps, args.warmup)
+            finally:
+                B.set_tile(0)
+            k["two_kernel_form_us"] = round(t2 * 1e3, 2)
+            contraction_ms.append(tl)
+        else:
+            k["kernel"] = "k_quantize_to_fp4, then k_gemm_fp4 (FP4 MFMA product + scale epilogue)"
+            contraction_ms.append(tg)
+        tq = max(t2 - tg, 1e-6)
+        k.update({"ternarize_us": round(tq * 1e3, 2), "gemm_us": round(tg * 1e3, 2),
+                  "ternarize_GBs": round((L.M * L.K * 2.5 + 2 * L.M) / (tq * 1e-3) / 1e9, 1),
+                  "gemm_TOPS": round(L.ops / (tg * 1e-3) / 1e12, 2), "path": _kernel_path_name(B, L.M, L.N, L.K)})
+        kern.append(k)
+    # the kernels that hold the contraction: per layer, the one-launch linear or the product kernel
+    avg_ms = sum(contraction_ms) / len(contraction_ms)
+    achieved = (ops / len(layers)) / (avg_ms * 1e-3) / 1e12
+    up_bytes = (layers[0].M * layers[0].K * 2 + layers[0].N * layers[0].rw * 4 + 2 * (layers[0].M + layers[0].N)
+                + 2 * layers[0].M * layers[0].N) if kern[0]["launches"] == 1 else layers[0].gemm_prepared_bytes()
+    roofline = {"bound": "mfma",
+                "kernel": "mean over the two layers of the kernel holding the contraction: "
+                          + "; ".join("%s: %s" % (k["layer"], "k_linear_fused" if k["launches"] == 1 else "k_gemm_fp4")
+                                      for k in kern),
                 "achieved": round(achieved, 2), "peak": PEAK_FP4_TOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_FP4_TOPS, 4), "frac_of_int8_peak": round(achieved / PEAK_INT8_TOPS, 4),
-                # the K = 768 -> N = 3072 layer mostly stores: fragments + weight bits + scales in, 25 MB of fp16 out
-                "up_layer_frac_of_hbm_peak": round(layers[0].gemm_prepared_bytes() / (kern[0]["gemm_us"] * 1e-6) / 1e9
-                                                   / PEAK_HBM_GBS, 4),
-                # HBM/fabric bytes per launch (mean of the two layers) from rocprofv3 --pmc FETCH_SIZE and
-                # WRITE_SIZE runs scaled by the copy probe (profiles/traffic_c2_ffn.md): algorithmic bytes
-                # are 20.4e6 (fragments + weight bits + scales in, fp16 out), i.e. nothing is re-read
+                # the K = 768 -> N = 3072 layer mostly stores: 25 MB of fp16 out of a 19 Gflop product
+                "up_layer_frac_of_hbm_peak": round(up_bytes / (contraction_ms[0] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                # HBM/fabric bytes per launch (mean of the two kernels) from rocprofv3 --pmc FETCH_SIZE and
+                # WRITE_SIZE runs scaled by the copy probe (profiles/traffic_c2_ffn.md)
                 "traffic": TRAFFIC_C2_GEMM_BYTES}
     out = {"metric": "BWTA linear effective TOPS (ternarize+pack+GEMM+epilogue), encoder FFN shapes",
            "value": round(value, 3), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

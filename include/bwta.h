@@ -253,6 +253,11 @@ int bwta_set_path(int path);
 int bwta_get_path(void);
 /* Which family AUTO resolves to for a shape: BWTA_PATH_POPC, BWTA_PATH_MFMA or BWTA_PATH_FP4. */
 int bwta_auto_path(int M, int N, int K);
+/* How many kernels bwta_linear launches for a shape under the current settings, given a dense
+ * (lda = K), 16-byte-aligned fp16 input: 1 where ternarisation, product and epilogue run as one
+ * kernel (short K), else 2.  Informational (benchmarks label their timings with it); 0 for a
+ * non-positive dimension. */
+int bwta_linear_launches(int M, int N, int K);
 /* Tuning hook for benchmark sweeps: force the FP4 kernel's per-wavefront tile (22, 21, 12, 11 =
  * blocks of 32 rows x 32 columns per wavefront; 23 = 22 at three wavefronts per SIMD), the
  * popcount decode kernel's row split (1000 + 16 * lanes per row + chunks per lane) or the

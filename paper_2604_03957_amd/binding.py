@@ -22,7 +22,7 @@ PATH_AUTO, PATH_POPC, PATH_MFMA, PATH_FP4 = 0, 1, 2, 3
 
 EXPORTS = ["bwta_plane_row_words", "bwta_workspace_bytes", "bwta_quantize_pack_act",
            "bwta_pack_weights", "bwta_gemm", "bwta_linear", "bwta_strerror", "bwta_last_hip_error",
-           "bwta_set_path", "bwta_get_path", "bwta_auto_path", "bwta_version", "bwta_set_tile",
+           "bwta_set_path", "bwta_get_path", "bwta_auto_path", "bwta_linear_launches", "bwta_version", "bwta_set_tile",
            "bwta_prepared_bytes", "bwta_prepare_act", "bwta_gemm_prepared", "bwta_gemm_grouped",
            "bwta_quantize_pack_bool", "bwta_matmul_tt", "bwta_prepare_weights", "bwta_act_scale",
            "bwta_prepare_act_autoscale", "bwta_matmul_bool_prepared"]
@@ -88,6 +88,8 @@ _lib.bwta_set_path.argtypes = [_c.c_int]
 _lib.bwta_get_path.restype = _c.c_int
 _lib.bwta_auto_path.restype = _c.c_int
 _lib.bwta_auto_path.argtypes = [_c.c_int, _c.c_int, _c.c_int]
+_lib.bwta_linear_launches.restype = _c.c_int
+_lib.bwta_linear_launches.argtypes = [_c.c_int, _c.c_int, _c.c_int]
 _lib.bwta_version.restype = _c.c_int
 _lib.bwta_set_tile.restype = _c.c_int
 _lib.bwta_set_tile.argtypes = [_c.c_int]
@@ -166,6 +168,10 @@ def get_path():
 
 def auto_path(M, N, K):
     return int(_lib.bwta_auto_path(M, N, K))
+
+
+def linear_launches(M, N, K):
+    return int(_lib.bwta_linear_launches(M, N, K))
 
 
 def set_tile(tile):

@@ -424,6 +424,17 @@ int bwta_auto_path(int M, int N, int K)
     return M > 1 ? BWTA_PATH_FP4 : BWTA_PATH_POPC;
 }
 
+int bwta_linear_launches(int M, int N, int K)
+{
+    if (M <= 0 || N <= 0 || K <= 0) return 0;
+    if (!fp4_uses_fragments(M, K)) return 2;
+    alignas(16) static const uint16_t dense[8] = {};  // stands for an aligned input; never read
+    uint16_t sink = 0;
+    bwta::GemmArgs g{nullptr, nullptr, nullptr, M, N, K, (int)bwta_plane_row_words(K),
+                     {nullptr, BWTA_SCALE_NONE}, {nullptr, BWTA_SCALE_NONE}, nullptr, &sink, N};
+    return bwta::linear_fused_supported(dense, K, g) ? 1 : 2;
+}
+
 int bwta_version(void) { return 1; }
 
 int bwta_set_tile(int tile)

@@ -594,16 +594,16 @@ hipError_t launch(const GemmArgs &g, const uint32_t *frag, int s_pad, hipStream_
 // A workgroup owns one strip of 32 tokens and 1/R of the channels.  It ternarises its strip straight
 // into LDS in MFMA operand order (all of K: at most 16 KiB), so the activation operand of every
 // MFMA comes from LDS and is shared by all channels; the R workgroups of a strip repeat that part.
-// Each wavefront then walks its channel blocks four at a time: the weight bits of a group are
+// Each wavefront then walks its channel blocks two at a time: the weight bits of a group are
 // loaded from global memory directly in operand layout (lane (r, h) takes four words of row r; the
 // fragments are produced here, so words are dealt to k steps in the order that makes those four
 // words adjacent), all of K at once, and requested a group ahead, so the K loop runs out of
 // registers and LDS and the wavefronts share no barrier after the first: their epilogues and
 // stores overlap the others' MFMAs.
-constexpr int FL_STRIP_HALFS = 32 * (32 * 4 + 8);  // room for the widest group
+constexpr int FL_STRIP_HALFS = 32 * (32 * 2 + 8);  // room for the widest group
 
 // word j of a 256-k chunk feeds k step j % 4 of the chunk on lane half j / 4
-template <int NCH, int FL_CB>  // 256-k chunks of K (1..4); channel blocks (of 32) per group: 1, 2 or 4
+template <int NCH, int FL_CB>  // 256-k chunks of K (1..4); channel blocks (of 32) per group: 1 or 2
 __global__ __launch_bounds__(256) void k_linear_fused(const uint16_t *__restrict__ A, int64_t lda, GemmArgs g, int R,
                                                       int cbw /* channel blocks per workgroup, a multiple of 4 FL_CB */)
 {
@@ -756,13 +756,14 @@ hipError_t launch_quantize_to_fp4(const void *A, int64_t lda, ScaleArg s_a, int 
 
 // One launch for the whole linear when K is short (see k_linear_fused).  The workgroups of a strip
 // each ternarise it again and a weight operand feeds a single MFMA, so the kernel's cost grows
-// about three times as fast with K as the two-kernel form's, while its fixed cost is 2 us lower;
-// measured at M = 4096 it wins up to K = 256 at N = 3072 (8.4 against 10.4 us) and up to K = 768 at
-// N = 768 (8.0 against 9.7 us), and is level or behind beyond.
+// faster with K and N than the two-kernel form's, while its fixed cost is 2 us lower.  Measured
+// over M = 512 .. 16384, N = 768 .. 11008, K = 256 .. 1024 it is ahead (by 3 to 35 %) or level for
+// K <= 768 up to N = 4096, and for K <= 1024 on small layers; at N = 11008 or longer K the two
+// kernels win.
 bool linear_fused_supported(const void *A, int64_t lda, const GemmArgs &g)
 {
     if (g_linear_fused == 0) return false;
-    const bool pays = g.K <= 256 || (g.K <= 768 && g.N <= 1024);
+    const bool pays = (g.K <= 768 && g.N <= 4096) || (g.K <= 1024 && g.N <= 1024 && g.M <= 2048);
     return (pays || g_linear_fused == 2) && g.K <= 1024 && g.M >= 256 && g.N >= 128 && g.out != nullptr &&
            g.acc == nullptr && ((uintptr_t)A % 16) == 0 && (lda % 8) == 0 && (g.K % 8) == 0;
 }
@@ -770,13 +771,18 @@ bool linear_fused_supported(const void *A, int64_t lda, const GemmArgs &g)
 hipError_t launch_linear_fused(const void *A, int64_t lda, const GemmArgs &g, hipStream_t st)
 {
     const int nstrips = (g.M + 31) / 32, ncb = (g.N + 31) / 32;
-    // channel splits (measured at M = 4096): about 1024 workgroups while K <= 256, where the repeated
-    // ternarisation is cheap, about 256 beyond; at most 64 channel blocks per workgroup
+    // Channel splits (measured at M = 1024 .. 4096): about 1024 workgroups while K <= 256, where the
+    // repeated ternarisation is cheap; beyond, 4 splits or what makes 256 workgroups, whichever is
+    // more; at most 64 channel blocks per workgroup.  Groups of two channel blocks: with several
+    // groups per wavefront the next group's weight bits arrive, and the other wavefronts' MFMAs run,
+    // while a group is scaled and stored (groups of 4 were 1 us slower at the benchmark's up layer).
     const int want_wgs = g.K <= 256 ? 1024 : 256;
-    int R = g_linear_fused_r > 0 ? g_linear_fused_r : (want_wgs + nstrips - 1) / nstrips;
+    int R = (want_wgs + nstrips - 1) / nstrips;
+    if (g.K > 256 && R < 4) R = 4;
+    if (g_linear_fused_r > 0) R = g_linear_fused_r;
     if (R < (ncb + 63) / 64) R = (ncb + 63) / 64;
     const int pw = ((ncb + R - 1) / R + 3) / 4;  // channel blocks per wavefront
-    const int CB = pw >= 4 ? 4 : pw >= 2 ? 2 : 1;
+    const int CB = pw >= 2 ? 2 : 1;
     const int cbw = 4 * ((pw + CB - 1) / CB * CB);
     if (cbw > 64) return hipErrorInvalidValue;
     R = (ncb + cbw - 1) / cbw;
@@ -788,8 +794,7 @@ hipError_t launch_linear_fused(const void *A, int64_t lda, const GemmArgs &g, hi
         hipLaunchKernelGGL((k_linear_fused<N_, C_>), grid, block, smem, st, (const uint16_t *)A, lda, g, R, cbw); \
         return hipGetLastError();                                                                                \
     }
-    BWTA_FL(1, 1) BWTA_FL(1, 2) BWTA_FL(1, 4) BWTA_FL(2, 1) BWTA_FL(2, 2) BWTA_FL(2, 4)
-    BWTA_FL(3, 1) BWTA_FL(3, 2) BWTA_FL(3, 4) BWTA_FL(4, 1) BWTA_FL(4, 2) BWTA_FL(4, 4)
+    BWTA_FL(1, 1) BWTA_FL(1, 2) BWTA_FL(2, 1) BWTA_FL(2, 2) BWTA_FL(3, 1) BWTA_FL(3, 2) BWTA_FL(4, 1) BWTA_FL(4, 2)
 #undef BWTA_FL
     return hipErrorInvalidValue;
 }
