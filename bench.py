@@ -27,7 +27,7 @@ if ROOT not in sys.path:
 PEAK_INT8_TOPS = 5000.0   # MI355X dense int8 MFMA, TOP/s
 PEAK_FP4_TOPS = 10100.0   # MI355X dense fp4 MFMA, TFLOP/s (the dtype the dominant kernel contracts in)
 PEAK_HBM_GBS = 8000.0     # MI355X HBM3E, GB/s
-TRAFFIC_C2_GEMM_BYTES = 22.6e6  # measured, see profiles/traffic_c2_ffn.md
+TRAFFIC_C2_GEMM_BYTES = 24.9e6  # measured, see profiles/traffic_c2_ffn.md
 PEAK_VALU_POPC_TOPS = 1258.0  # 256 CU * 64 lanes * 2.4 GHz * 32 MAC per 2 VALU ops * 2 ops/MAC
 
 
