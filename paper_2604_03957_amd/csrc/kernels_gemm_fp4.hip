@@ -603,16 +603,17 @@ hipError_t launch(const GemmArgs &g, const uint32_t *frag, int s_pad, hipStream_
 constexpr int FL_STRIP_HALFS = 32 * (32 * 2 + 8);  // room for the widest group
 
 // word j of a 256-k chunk feeds k step j % 4 of the chunk on lane half j / 4
-template <int NCH, int FL_CB>  // 256-k chunks of K (1..4); channel blocks (of 32) per group: 1 or 2
-__global__ __launch_bounds__(256) void k_linear_fused(const uint16_t *__restrict__ A, int64_t lda, GemmArgs g, int R,
-                                                      int cbw /* channel blocks per workgroup, a multiple of 4 FL_CB */)
+template <int NCH, int FL_CB, int NWV>  // 256-k chunks of K (1..4); channel blocks (of 32) per group: 1 or 2; wavefronts: 4 or 8
+__global__ __launch_bounds__(64 * NWV) void k_linear_fused(const uint16_t *__restrict__ A, int64_t lda, GemmArgs g, int R,
+                                                      int cbw /* channel blocks per workgroup, a multiple of NWV FL_CB */)
 {
     extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
     constexpr int NSTEP = 4 * NCH;
+    constexpr int NT = 64 * NWV, WPI = NT / 128, NIT = 8 * NCH / WPI;  // threads; plane words per row and pass; passes
     uint32_t *sA = smem;                                   // [NSTEP][64 lanes][4 dwords]
     float *s_sa = (float *)(smem + NSTEP * 256);           // [32] token scales
     float *s_sw = s_sa + 32;                               // [32 cbw] channel scales
-    uint16_t *strips = (uint16_t *)(s_sw + 32 * cbw);      // [4 wavefronts][FL_STRIP_HALFS]
+    uint16_t *strips = (uint16_t *)(s_sw + 32 * cbw);      // [NWV wavefronts][FL_STRIP_HALFS]
 
     // the R workgroups of a strip sit 8 ids apart: same XCD, so the strip's second reader hits its L2
     const int nstrips = (g.M + 31) >> 5;
@@ -624,7 +625,7 @@ __global__ __launch_bounds__(256) void k_linear_fused(const uint16_t *__restrict
     const int m0 = 32 * strip_id;
     const int cb0 = split * cbw;               // first channel block of this workgroup
     const int ncb = (g.N + 31) >> 5;           // channel blocks in all
-    const int per_wave = cbw >> 2;             // channel blocks per wavefront, a multiple of FL_CB
+    const int per_wave = cbw / NWV;            // channel blocks per wavefront, a multiple of FL_CB
     const int wcb0 = cb0 + wave * per_wave;    // first channel block of this wavefront
 
     // ---- requests, smallest first: scales, the strip's activations, the first group's weight bits
@@ -634,18 +635,18 @@ __global__ __launch_bounds__(256) void k_linear_fused(const uint16_t *__restrict
     const bool have_sa = g.s_a.mode != 0 && g.s_a.ptr != nullptr;
     const uint16_t sa_bits = *(have_sa ? g.s_a.ptr + (g.s_a.mode == 1 ? 0 : mc) : A);
     const bool have_sw = g.s_w.mode != 0 && g.s_w.ptr != nullptr;
-    constexpr int SW_PER = 8;  // 8 x 256 channel scales at most (cbw <= 64)
+    constexpr int SW_PER = 2048 / NT;  // 2048 channel scales at most (cbw <= 64)
     uint16_t sw_bits[SW_PER];
 #pragma unroll
     for (int i = 0; i < SW_PER; ++i) {
-        const int n = 32 * cb0 + tid + 256 * i;
-        const bool want = tid + 256 * i < 32 * cbw && n < g.N && have_sw;
+        const int n = 32 * cb0 + tid + NT * i;
+        const bool want = tid + NT * i < 32 * cbw && n < g.N && have_sw;
         sw_bits[i] = *(want ? g.s_w.ptr + (g.s_w.mode == 1 ? 0 : n) : A);
     }
-    uint4 x[NSTEP];
+    uint4 x[NIT];
 #pragma unroll
-    for (int it = 0; it < NSTEP; ++it) {
-        const int q = 2 * it + (quad >> 5), k0 = 32 * q + 8 * j;
+    for (int it = 0; it < NIT; ++it) {
+        const int q = WPI * it + (quad >> 5), k0 = 32 * q + 8 * j;
         const bool inb = m < g.M && k0 < g.K;  // lanes outside re-read the first bytes and drop them
         x[it] = *(const uint4 *)(A + (inb ? (int64_t)m * lda + k0 : 0));
     }
@@ -673,12 +674,12 @@ __global__ __launch_bounds__(256) void k_linear_fused(const uint16_t *__restrict
     if ((quad >> 5) == 0 && j == 0) s_sa[row] = m < g.M ? (have_sa ? half_bits_to_float(sa_bits) : 1.0f) : 0.0f;
 #pragma unroll
     for (int i = 0; i < SW_PER; ++i) {
-        const int e = tid + 256 * i, n = 32 * cb0 + e;
+        const int e = tid + NT * i, n = 32 * cb0 + e;
         if (e < 32 * cbw) s_sw[e] = n < g.N ? (have_sw ? half_bits_to_float(sw_bits[i]) : 1.0f) : 0.0f;
     }
 #pragma unroll
-    for (int it = 0; it < NSTEP; ++it) {
-        const int q = 2 * it + (quad >> 5), k0 = 32 * q + 8 * j;
+    for (int it = 0; it < NIT; ++it) {
+        const int q = WPI * it + (quad >> 5), k0 = 32 * q + 8 * j;
         uint4 v = x[it];
         if (!(m < g.M && k0 < g.K)) v = make_uint4(0, 0, 0, 0);
         const uint32_t D = fragment_dword(v, thr, j);
@@ -756,14 +757,14 @@ hipError_t launch_quantize_to_fp4(const void *A, int64_t lda, ScaleArg s_a, int 
 
 // One launch for the whole linear when K is short (see k_linear_fused).  The workgroups of a strip
 // each ternarise it again and a weight operand feeds a single MFMA, so the kernel's cost grows
-// faster with K and N than the two-kernel form's, while its fixed cost is 2 us lower.  Measured
-// over M = 512 .. 16384, N = 768 .. 11008, K = 256 .. 1024 it is ahead (by 3 to 35 %) or level for
-// K <= 768 up to N = 4096, and for K <= 1024 on small layers; at N = 11008 or longer K the two
-// kernels win.
+// faster with K than the two-kernel form's, while its fixed cost is 2 us lower.  Measured over
+// M = 512 .. 16384, N = 768 .. 11008, K = 256 .. 1024 it is ahead everywhere for K <= 768 (by 5 to
+// 40 %: 13.1 -> 10.4 us at 4096 x 3072 x 768, 17.8 -> 11.3 us at 16384 x 768 x 768) and for K = 1024
+// up to N = 4096 and M = 8192; beyond, the two kernels win.
 bool linear_fused_supported(const void *A, int64_t lda, const GemmArgs &g)
 {
     if (g_linear_fused == 0) return false;
-    const bool pays = (g.K <= 768 && g.N <= 4096) || (g.K <= 1024 && g.N <= 1024 && g.M <= 2048);
+    const bool pays = g.K <= 768 || (g.N <= 4096 && g.M <= 8192);
     return (pays || g_linear_fused == 2) && g.K <= 1024 && g.M >= 256 && g.N >= 128 && g.out != nullptr &&
            g.acc == nullptr && ((uintptr_t)A % 16) == 0 && (lda % 8) == 0 && (g.K % 8) == 0;
 }
@@ -771,27 +772,33 @@ bool linear_fused_supported(const void *A, int64_t lda, const GemmArgs &g)
 hipError_t launch_linear_fused(const void *A, int64_t lda, const GemmArgs &g, hipStream_t st)
 {
     const int nstrips = (g.M + 31) / 32, ncb = (g.N + 31) / 32;
-    // Channel splits (measured at M = 1024 .. 4096): about 1024 workgroups while K <= 256, where the
-    // repeated ternarisation is cheap; beyond, 4 splits or what makes 256 workgroups, whichever is
-    // more; at most 64 channel blocks per workgroup.  Groups of two channel blocks: with several
-    // groups per wavefront the next group's weight bits arrive, and the other wavefronts' MFMAs run,
-    // while a group is scaled and stored (groups of 4 were 1 us slower at the benchmark's up layer).
-    const int want_wgs = g.K <= 256 ? 1024 : 256;
-    int R = (want_wgs + nstrips - 1) / nstrips;
-    if (g.K > 256 && R < 4) R = 4;
+    // Workgroups of 8 wavefronts (4 where a workgroup has fewer than 8 channel blocks) and as many
+    // channel splits as make about 256 workgroups, i.e. two wavefronts per SIMD; at most 64 channel
+    // blocks per workgroup.  Measured at M = 1024 .. 8192: against 4 wavefronts and twice the splits
+    // the strip is ternarised half as often for the same number of wavefronts (10.3 against 11.7 us
+    // at the benchmark's up layer, 16.3 against 20.3 us at M = 8192).  Groups of two channel blocks:
+    // with several groups per wavefront the next group's weight bits arrive, and the other
+    // wavefronts' MFMAs run, while a group is scaled and stored (groups of 4 were 1 us slower).
+    int R = (256 + nstrips - 1) / nstrips;
     if (g_linear_fused_r > 0) R = g_linear_fused_r;
+    if (R > ncb) R = ncb;
+    const int NWV = (ncb + R - 1) / R >= 8 ? 8 : 4;
     if (R < (ncb + 63) / 64) R = (ncb + 63) / 64;
-    const int pw = ((ncb + R - 1) / R + 3) / 4;  // channel blocks per wavefront
+    const int pw = ((ncb + R - 1) / R + NWV - 1) / NWV;  // channel blocks per wavefront
     const int CB = pw >= 2 ? 2 : 1;
-    const int cbw = 4 * ((pw + CB - 1) / CB * CB);
+    const int cbw = NWV * ((pw + CB - 1) / CB * CB);
     if (cbw > 64) return hipErrorInvalidValue;
     R = (ncb + cbw - 1) / cbw;
     const int nch = (g.rw + 7) / 8;
-    const size_t smem = (size_t)nch * 4 * 1024 + (32 + 32 * cbw) * 4 + 4 * FL_STRIP_HALFS * 2;
-    const dim3 grid((unsigned)((nstrips + 7) / 8 * 8 * R)), block(256);
+    const size_t smem = (size_t)nch * 4 * 1024 + (32 + 32 * cbw) * 4 + (size_t)NWV * FL_STRIP_HALFS * 2;
+    const dim3 grid((unsigned)((nstrips + 7) / 8 * 8 * R)), block(64 * NWV);
 #define BWTA_FL(N_, C_)                                                                                          \
-    if (nch == N_ && CB == C_) {                                                                                 \
-        hipLaunchKernelGGL((k_linear_fused<N_, C_>), grid, block, smem, st, (const uint16_t *)A, lda, g, R, cbw); \
+    if (nch == N_ && CB == C_ && NWV == 4) {                                                                     \
+        hipLaunchKernelGGL((k_linear_fused<N_, C_, 4>), grid, block, smem, st, (const uint16_t *)A, lda, g, R, cbw); \
+        return hipGetLastError();                                                                                \
+    }                                                                                                            \
+    if (nch == N_ && CB == C_ && NWV == 8) {                                                                     \
+        hipLaunchKernelGGL((k_linear_fused<N_, C_, 8>), grid, block, smem, st, (const uint16_t *)A, lda, g, R, cbw); \
         return hipGetLastError();                                                                                \
     }
     BWTA_FL(1, 1) BWTA_FL(1, 2) BWTA_FL(2, 1) BWTA_FL(2, 2) BWTA_FL(3, 1) BWTA_FL(3, 2) BWTA_FL(4, 1) BWTA_FL(4, 2)
