@@ -385,6 +385,28 @@ def test_linear_one_launch_short_k(M, N, K, hook):
     assert same_half(out, want)
 
 
+@pytest.mark.parametrize("K", [200, 504, 760, 1000])
+@pytest.mark.parametrize("N", [250, 440, 512, 1000])
+def test_linear_one_launch_every_kernel_instance(N, K):
+    """With two channel splits forced, N = 250 / 440 / 512 / 1000 leaves a workgroup 4 / 7 / 8 / 16
+    channel blocks: workgroups of 4 or 8 wavefronts with groups of one or two blocks; K = 200 ..
+    1000 gives one to four chunks of 256 k.  Together every instance of the kernel runs, on ragged
+    M, N and K."""
+    M = 300
+    _say("one-launch linear, instance sweep", M, N, K)
+    A, s = _activation_case(900 + N + K, M, K)
+    w = synth.binary_pm1(36, N + K, (N, K))
+    s_w = synth.scales(36, 8, N)
+    _, _, want = oracle.linear(A, s, w, s_w)
+    B.set_tile(902)
+    try:
+        assert B.linear_launches(M, N, K) == 1
+        out = gpu_linear(A, s, gpu_pack_weights(w), s_w, N, path=B.PATH_FP4)
+    finally:
+        B.set_tile(0)
+    assert same_half(out, want)
+
+
 def test_linear_one_launch_scale_modes_and_strides():
     """The one-launch kernel with layerwise (scalar) scales, with no scales at all, and with strided
     input and output (nothing written past N)."""
