@@ -27,7 +27,7 @@ if ROOT not in sys.path:
 PEAK_INT8_TOPS = 5000.0   # MI355X dense int8 MFMA, TOP/s
 PEAK_FP4_TOPS = 10100.0   # MI355X dense fp4 MFMA, TFLOP/s (the dtype the dominant kernel contracts in)
 PEAK_HBM_GBS = 8000.0     # MI355X HBM3E, GB/s
-TRAFFIC_C2_GEMM_BYTES = 24.9e6  # measured, see profiles/traffic_c2_ffn.md
+TRAFFIC_C2_DOMINANT_BYTES = 34.0e6  # k_linear_fused on the up layer; measured, see profiles/traffic_c2_ffn.md
 PEAK_VALU_POPC_TOPS = 1258.0  # 256 CU * 64 lanes * 2.4 GHz * 32 MAC per 2 VALU ops * 2 ops/MAC
 
 
@@ -247,22 +247,35 @@ def run_c2(args, torch, B, synth):
                   "ternarize_GBs": round((L.M * L.K * 2.5 + 2 * L.M) / (tq * 1e-3) / 1e9, 1),
                   "gemm_TOPS": round(L.ops / (tg * 1e-3) / 1e12, 2), "path": _kernel_path_name(B, L.M, L.N, L.K)})
         kern.append(k)
-    # the kernels that hold the contraction: per layer, the one-launch linear or the product kernel
-    avg_ms = sum(contraction_ms) / len(contraction_ms)
-    achieved = (ops / len(layers)) / (avg_ms * 1e-3) / 1e12
-    up_bytes = (layers[0].M * layers[0].K * 2 + layers[0].N * layers[0].rw * 4 + 2 * (layers[0].M + layers[0].N)
-                + 2 * layers[0].M * layers[0].N) if kern[0]["launches"] == 1 else layers[0].gemm_prepared_bytes()
+    # the kernels that hold the contraction: per layer, the one-launch linear or the product kernel;
+    # the dominant one is the longer of the two (the up layer's: it writes 25 MB of fp16)
+    names = ["k_linear_fused" if k["launches"] == 1 else "k_gemm_fp4" for k in kern]
+    dom = max(range(len(layers)), key=lambda i: contraction_ms[i])
+    L = layers[dom]
+    achieved = L.ops / (contraction_ms[dom] * 1e-3) / 1e12
+    if kern[dom]["launches"] == 1:  # fp16 activations, weight bits, scales in; fp16 out
+        alg_bytes = L.M * L.K * 2 + L.N * L.rw * 4 + 2 * (L.M + L.N) + 2 * L.M * L.N
+    else:
+        alg_bytes = L.gemm_prepared_bytes()
+    other = [{"layer": kern[i]["layer"], "kernel": names[i], "us": round(contraction_ms[i] * 1e3, 2),
+              "achieved": round(layers[i].ops / (contraction_ms[i] * 1e-3) / 1e12, 2),
+              "frac": round(layers[i].ops / (contraction_ms[i] * 1e-3) / 1e12 / PEAK_FP4_TOPS, 4)}
+             for i in range(len(layers)) if i != dom]
     roofline = {"bound": "mfma",
-                "kernel": "mean over the two layers of the kernel holding the contraction: "
-                          + "; ".join("%s: %s" % (k["layer"], "k_linear_fused" if k["launches"] == 1 else "k_gemm_fp4")
-                                      for k in kern),
+                "kernel": "%s on %s (%s), %.2f us per launch" % (names[dom], kern[dom]["layer"],
+                                                                "ternarise + FP4 MFMA product + scale epilogue"
+                                                                if kern[dom]["launches"] == 1 else
+                                                                "FP4 MFMA product + scale epilogue",
+                                                                contraction_ms[dom] * 1e3),
                 "achieved": round(achieved, 2), "peak": PEAK_FP4_TOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_FP4_TOPS, 4), "frac_of_int8_peak": round(achieved / PEAK_INT8_TOPS, 4),
-                # the K = 768 -> N = 3072 layer mostly stores: 25 MB of fp16 out of a 19 Gflop product
-                "up_layer_frac_of_hbm_peak": round(up_bytes / (contraction_ms[0] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
-                # HBM/fabric bytes per launch (mean of the two kernels) from rocprofv3 --pmc FETCH_SIZE and
-                # WRITE_SIZE runs scaled by the copy probe (profiles/traffic_c2_ffn.md)
-                "traffic": TRAFFIC_C2_GEMM_BYTES}
+                # this layer mostly stores: 25 MB of fp16 out of a 19 Gflop product
+                "algorithmic_bytes": alg_bytes,
+                "frac_of_hbm_peak": round(alg_bytes / (contraction_ms[dom] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                # HBM/fabric bytes per launch of this kernel from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
+                # runs scaled by the copy probe (profiles/traffic_c2_ffn.md)
+                "traffic": TRAFFIC_C2_DOMINANT_BYTES if names[dom] == "k_linear_fused" else None,
+                "other_contraction_kernels": other}
     out = {"metric": "BWTA linear effective TOPS (ternarize+pack+GEMM+epilogue), encoder FFN shapes",
            "value": round(value, 3), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
