@@ -407,6 +407,22 @@ def test_linear_one_launch_every_kernel_instance(N, K):
     assert same_half(out, want)
 
 
+def test_linear_one_launch_seeded_random_shapes():
+    """40 seeded random shapes (M 256..1500, N 128..2500, K 8..1024 in steps of 8) through the
+    dispatcher's own choice of launch form, split count and kernel instance."""
+    rng = np.random.default_rng(20260404)
+    for case in range(40):
+        M, N, K = int(rng.integers(256, 1501)), int(rng.integers(128, 2501)), 8 * int(rng.integers(1, 129))
+        _say("one-launch linear, random shape", case, M, N, K)
+        A, s = _activation_case(2000 + case, M, K)
+        w = synth.binary_pm1(37, case, (N, K))
+        s_w = synth.scales(37, 100 + case, N)
+        _, _, want = oracle.linear(A, s, w, s_w)
+        assert B.linear_launches(M, N, K) == 1
+        out = gpu_linear(A, s, gpu_pack_weights(w), s_w, N)
+        assert same_half(out, want), (case, M, N, K)
+
+
 def test_linear_one_launch_scale_modes_and_strides():
     """The one-launch kernel with layerwise (scalar) scales, with no scales at all, and with strided
     input and output (nothing written past N)."""
