@@ -852,8 +852,6 @@ hipError_t launch_gemm_fp4(const GemmArgs &g, uint32_t *frag, bool frag_ready, h
     case 12: return launch<1, 2, 2, 2, 3, false>(g, frag, s_pad, st);
     case 11: return launch<1, 1, 2, 2, 4, false>(g, frag, s_pad, st);
     case 13: return launch<1, 3, 4, 1, 2, false>(g, frag, s_pad, st);
-    case 2216: return launch<2, 2, 2, 2, 2, false, 1, 16>(g, frag, s_pad, st);
-    case 22216: return launch<2, 2, 2, 2, 2, false, 2, 16>(g, frag, s_pad, st);
     case 222: return launch<2, 2, 2, 2, 2, false, 2>(g, frag, s_pad, st);
     default: break;
     }

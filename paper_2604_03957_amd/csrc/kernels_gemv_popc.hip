@@ -225,8 +225,8 @@ hipError_t launch_m(const GemvBatch &b, int count, const GemvShape &sh, hipStrea
             return launch_t<MT, G_, NCH_>(b, count, sh, st);                                       \
     }
     BWTA_GEMV_FORCE(8, 4) BWTA_GEMV_FORCE(16, 2) BWTA_GEMV_FORCE(32, 1) BWTA_GEMV_FORCE(16, 6)
-    BWTA_GEMV_FORCE(32, 3) BWTA_GEMV_FORCE(64, 2) BWTA_GEMV_FORCE(8, 11) BWTA_GEMV_FORCE(16, 4)
-    BWTA_GEMV_FORCE(32, 2) BWTA_GEMV_FORCE(64, 1) BWTA_GEMV_FORCE(32, 4)
+    BWTA_GEMV_FORCE(32, 3) BWTA_GEMV_FORCE(8, 11) BWTA_GEMV_FORCE(16, 4) BWTA_GEMV_FORCE(32, 2)
+    BWTA_GEMV_FORCE(32, 4)
 #undef BWTA_GEMV_FORCE
     // Measured on MI355X: few chunks per lane (small activation register footprint, more
     // wavefronts in flight) beats few lanes per row, so rows are spread over up to 32 lanes
@@ -243,9 +243,10 @@ hipError_t launch_m(const GemvBatch &b, int count, const GemvShape &sh, hipStrea
     BWTA_GEMV_TRY(32, 2)
     BWTA_GEMV_TRY(32, 3)
     BWTA_GEMV_TRY(32, 4)
-    BWTA_GEMV_TRY(64, 1)
-    BWTA_GEMV_TRY(64, 2)
 #undef BWTA_GEMV_TRY
+    if constexpr (MT == 8) {  // two chunks per lane at most: the longest rows go over all 64 lanes
+        if (C4 <= 128) return launch_t<MT, 64, 2>(b, count, sh, st);
+    }
     return hipErrorInvalidValue;
 }
 
