@@ -262,9 +262,10 @@ int bwta_auto_path(int M, int N, int K);
  * kernel (short K), else 2.  Informational (benchmarks label their timings with it); 0 for a
  * non-positive dimension. */
 int bwta_linear_launches(int M, int N, int K);
-/* Tuning hook for benchmark sweeps: force the FP4 kernel's per-wavefront tile (22, 21, 12, 11 =
- * blocks of 32 rows x 32 columns per wavefront; 23 = 22 at three wavefronts per SIMD), the
- * popcount decode kernel's row split (1000 + 16 * lanes per row + chunks per lane) or the
+/* Tuning hook for benchmark sweeps: force the FP4 kernel's per-wavefront tile (22, 21, 12, 11, 13
+ * = blocks of 32 rows x 32 columns per wavefront; 23 = 22 at three wavefronts per SIMD; 222 = 22
+ * with K split over two groups of wavefronts), the popcount decode kernel's row split (1000 + 16 *
+ * lanes per row (8, 16, 32) + chunks per lane; ignored where the registers cannot hold it) or the
  * matrix-core decode kernel's work split (2000 + 1024 * ring depth (2..4) + 64 * chunks per
  * wavefront (1..4) + tiles per workgroup (rounded up to a multiple of the ring depth, fewer if LDS
  * does not hold their partials)), or where bwta_linear runs as a single launch (900 never, 901
