@@ -423,6 +423,41 @@ def test_linear_one_launch_seeded_random_shapes():
         assert same_half(out, want), (case, M, N, K)
 
 
+def test_every_entry_and_family_seeded_random_shapes():
+    """60 seeded random problems (prefill-sized with any K, short K, decode-sized) with planted
+    ties, infinities, NaN, -0 and now and then an invalid token scale: bwta_linear as dispatched,
+    and bwta_gemm on the dispatcher's choice and on each kernel family, int32 and fp16."""
+    rng = np.random.default_rng(20260405)
+    for case in range(60):
+        kind = case % 3
+        if kind == 0:
+            M, N, K = int(rng.integers(129, 1200)), int(rng.integers(1, 1500)), int(rng.integers(1, 3000))
+        elif kind == 1:
+            M, N, K = int(rng.integers(256, 3000)), int(rng.integers(128, 3000)), 8 * int(rng.integers(1, 129))
+        else:
+            M, N, K = int(rng.integers(1, 129)), int(rng.integers(1, 2000)), int(rng.integers(1, 12000))
+        _say("random problem", case, M, N, K)
+        A = (synth.gaussian(9000 + case, 1, M * K) * float(rng.uniform(0.01, 30))).astype(np.float16).reshape(M, K)
+        s = oracle.act_scale(A)
+        if M * K > 8:
+            flat = A.reshape(-1)
+            idx = rng.integers(0, flat.size, 6)
+            flat[idx[0]] = np.float16(0.5) * s[idx[0] // K]
+            flat[idx[1]] = -(np.float16(0.5) * s[idx[1] // K])
+            flat[idx[2]], flat[idx[3]], flat[idx[4]], flat[idx[5]] = np.inf, -np.inf, np.nan, -0.0
+        if case % 4 == 0:
+            s[int(rng.integers(0, M))] = np.float16([0.0, -1.0, np.inf, np.nan][(case // 4) % 4])
+        w = synth.binary_pm1(9100 + case, 2, (N, K))
+        s_w = synth.scales(9200 + case, 3, N)
+        t, acc_want, want = oracle.linear(A, s, w, s_w)
+        wsign = gpu_pack_weights(w)
+        assert same_half(gpu_linear(A, s, wsign, s_w, N), want), (case, M, N, K)
+        mask, sign, _ = oracle.pack_act(t)
+        for path in [B.PATH_AUTO] + PATHS:
+            acc, out = gpu_gemm(mask, sign, wsign, s, s_w, M, N, K, path=path)
+            assert np.array_equal(acc, acc_want) and same_half(out, want), (case, M, N, K, path)
+
+
 def test_linear_one_launch_scale_modes_and_strides():
     """The one-launch kernel with layerwise (scalar) scales, with no scales at all, and with strided
     input and output (nothing written past N)."""
