@@ -365,7 +365,8 @@ def test_linear_ragged_shapes_and_special_values(M, N, K, path):
 
 
 @pytest.mark.parametrize("hook", [0, 901, 902, 903, 906, 912])
-@pytest.mark.parametrize("M,N,K", [(256, 128, 128), (300, 260, 768), (1000, 3072, 768), (289, 1000, 1000), (700, 513, 1024), (257, 130, 136)])
+@pytest.mark.parametrize("M,N,K", [(256, 128, 128), (300, 260, 768), (1000, 3072, 768), (289, 1000, 1000), (700, 513, 1024), (257, 130, 136),
+                                   (129, 130, 136), (200, 513, 768)])
 def test_linear_one_launch_short_k(M, N, K, hook):
     """bwta_linear as a single kernel (K <= 1024): every chunk count, channel splits forced to
     1, 2, 3, 6 and 12 as well as the launcher's own choice (which makes every group width appear; 0 = the
