@@ -120,8 +120,9 @@ int bwta_gemm(const uint32_t *mask, const uint32_t *sign, const uint32_t *wsign,
  * The whole layer on fp16 activations: ternarise + pack + product + scale epilogue
  * (the BWTA linear equation end to end).  A fp16 [M, lda]; wsign from bwta_pack_weights;
  * out fp16 [M, ldo].  s_a is used both as the ternarisation scale and in the epilogue.
- * Runs as two kernels (ternarise into the workspace, then the product) or, for short K on
- * prefill-sized M with 16-byte-aligned rows, as one kernel that never touches the workspace;
+ * Runs as two kernels (ternarise into the workspace, then the product) or, for short K
+ * (at most 1024) with 16-byte-aligned rows and at least two tokens, as one kernel that never
+ * touches the workspace;
  * the result is the same bit for bit (see bwta_linear_launches).  The workspace is required
  * either way.
  */

@@ -155,7 +155,7 @@ int bwta_linear(const void *A, int64_t lda, const void *s_a, int a_scale_mode, c
     if (!aligned(A, 2) || !aligned(wsign, 16)) return BWTA_ERR_ALIGN;
     if (!workspace || workspace_bytes < bwta_workspace_bytes(M, N, K)) return BWTA_ERR_WORKSPACE;
     if (!aligned(workspace, 256)) return BWTA_ERR_ALIGN;
-    if (fp4_uses_fragments(M, K)) {
+    if (resolve_path(M, N, K) == BWTA_PATH_FP4) {
         bwta::GemmArgs g{nullptr, nullptr, wsign, M, N, K, (int)bwta_plane_row_words(K),
                          {(const uint16_t *)s_a, s_a ? a_scale_mode : BWTA_SCALE_NONE},
                          {(const uint16_t *)s_w, s_w ? w_scale_mode : BWTA_SCALE_NONE},
@@ -427,7 +427,7 @@ int bwta_auto_path(int M, int N, int K)
 int bwta_linear_launches(int M, int N, int K)
 {
     if (M <= 0 || N <= 0 || K <= 0) return 0;
-    if (!fp4_uses_fragments(M, K)) return 2;
+    if (resolve_path(M, N, K) != BWTA_PATH_FP4) return 2;
     alignas(16) static const uint16_t dense[8] = {};  // stands for an aligned input; never read
     uint16_t sink = 0;
     bwta::GemmArgs g{nullptr, nullptr, nullptr, M, N, K, (int)bwta_plane_row_words(K),

@@ -765,7 +765,7 @@ bool linear_fused_supported(const void *A, int64_t lda, const GemmArgs &g)
 {
     if (g_linear_fused == 0) return false;
     const bool pays = g.K <= 768 || (g.N <= 4096 && g.M <= 8192);
-    return (pays || g_linear_fused == 2) && g.K <= 1024 && g.M >= 129 && g.N >= 128 && g.out != nullptr &&
+    return (pays || g_linear_fused == 2) && g.K <= 1024 && g.N >= 128 && g.out != nullptr &&
            g.acc == nullptr && ((uintptr_t)A % 16) == 0 && (lda % 8) == 0 && (g.K % 8) == 0;
 }
 

@@ -45,7 +45,8 @@ def test_path_selection():
     assert B.auto_path(2048, 4096, 4096) in (B.PATH_MFMA, B.PATH_FP4)
     # launches of bwta_linear: one kernel for short K on prefill shapes, two otherwise; the hook turns it off
     assert B.linear_launches(4096, 3072, 768) == 1 and B.linear_launches(4096, 768, 3072) == 2
-    assert B.linear_launches(16, 768, 768) == 2 and B.linear_launches(16384, 11008, 1024) == 2
+    assert B.linear_launches(1, 768, 768) == 2 and B.linear_launches(16384, 11008, 1024) == 2
+    assert B.linear_launches(16, 768, 768) == 1
     assert B.linear_launches(0, 8, 8) == 0 and B.linear_launches(8, 8, -1) == 0
     B.set_tile(900)
     try:

@@ -366,7 +366,7 @@ def test_linear_ragged_shapes_and_special_values(M, N, K, path):
 
 @pytest.mark.parametrize("hook", [0, 901, 902, 903, 906, 912])
 @pytest.mark.parametrize("M,N,K", [(256, 128, 128), (300, 260, 768), (1000, 3072, 768), (289, 1000, 1000), (700, 513, 1024), (257, 130, 136),
-                                   (129, 130, 136), (200, 513, 768)])
+                                   (129, 130, 136), (200, 513, 768), (2, 130, 136), (16, 513, 768), (100, 3072, 1000)])
 def test_linear_one_launch_short_k(M, N, K, hook):
     """bwta_linear as a single kernel (K <= 1024): every chunk count, channel splits forced to
     1, 2, 3, 6 and 12 as well as the launcher's own choice (which makes every group width appear; 0 = the
@@ -374,7 +374,7 @@ def test_linear_one_launch_short_k(M, N, K, hook):
     ragged M and N, special values, an invalid token scale."""
     _say("one-launch linear", M, N, K, "hook", hook)
     A, s = _activation_case(500 + M, M, K)
-    s[5] = np.float16(0.0)
+    s[min(5, M - 1)] = np.float16(0.0)
     w = synth.binary_pm1(33, M + N, (N, K))
     s_w = synth.scales(33, 7, N)
     _, _, want = oracle.linear(A, s, w, s_w)
