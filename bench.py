@@ -606,7 +606,8 @@ def run_short_k(args, torch, B, synth):
     (the dispatcher's choice where it pays) and as ternarise + product (forced with the tuning hook)."""
     base = synth.config2("up")
     rows = []
-    for (M, N, K) in [(4096, 768, 768), (4096, 768, 256), (4096, 3072, 256), (1024, 768, 768), (4096, 3072, 768)]:
+    for (M, N, K) in [(4096, 768, 768), (4096, 768, 256), (4096, 3072, 256), (1024, 768, 768), (4096, 3072, 768),
+                      (128, 768, 768), (16, 3072, 768)]:
         A = np.ascontiguousarray(np.tile(base["A"], (1, 2))[:M, :K])
         c = dict(M=M, N=N, K=K, A=A, s_a=base["s_a"][:M], w=synth.binary_pm1(8, N + K, (N, K)), s_w=synth.scales(8, 4, N),
                  name="short_k")
