@@ -670,7 +670,7 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
         sys.exit(3)
     from paper_2604_03957_amd import binding as B
-    from paper_2604_03957_amd import synth
+    import synth
     torch.cuda.set_device(0)
     run = {"c2_ffn": run_c2, "c1_tiny": run_c1, "c3_prefill": run_c3, "c4_decode": run_c4,
            "c5_block": run_c5, "attn": run_attn, "prep": run_prep, "short_k": run_short_k,

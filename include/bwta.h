@@ -106,6 +106,8 @@ int bwta_pack_weights(const void *W, int w_dtype, int64_t ldw, int N, int K, uin
  *               bwta_pack_weights (the sign packer).  No mask plane is read; kernels that need
  *               one get it built in the workspace.
  *   wsign       u32 [N, row_words].
+ *   s_a, s_w    fp16 scales read per a_scale_mode / w_scale_mode (one per token / per channel with
+ *               VECTOR, one value with SCALAR, ignored with NONE).
  *   acc         optional out, int32 [M, N] dense (leading dimension N).
  *   out         optional out, fp16 [M, ldo], ldo >= N.  At least one of acc / out.
  *   workspace   scratch of at least bwta_workspace_bytes(M, N, K) bytes, 256-byte aligned;
@@ -134,18 +136,28 @@ int bwta_linear(const void *A, int64_t lda, const void *s_a, int a_scale_mode,
 /*
  * The two halves of bwta_linear as separate calls, so that one ternarisation can feed several
  * weight matrices (Q/K/V, gate/up): bwta_prepare_act ternarises fp16 activations (same rule and
- * arguments as bwta_quantize_pack_act with FP16 input) into `prepared`, an opaque device buffer
- * of bwta_prepared_bytes(M, K) bytes, 256-byte aligned, laid out for whichever contraction
- * kernel the current path selects for M tokens; bwta_gemm_prepared then computes
- * out = fp16(s_w * s_a * (sign(W) (x) ternary(A))) from it exactly like bwta_gemm.  The path
- * setting must not change between the two calls.  `prepared` is only read by the second call.
+ * arguments as bwta_quantize_pack_act with FP16 input) into `prepared`, a device buffer of
+ * bwta_prepared_bytes(M, K) bytes, 256-byte aligned, and writes to *prepared_format (a HOST int,
+ * required) which of two layouts it chose there: BWTA_PREPARED_PLANES (the two canonical bit
+ * planes, for the decode-sized kernels) or BWTA_PREPARED_FP4 (E2M1 fragments in matrix-core operand
+ * order, for the tiled kernel).  The choice depends on M, K and the path setting at the time of the
+ * call (bwta_prepared_format tells it in advance).  bwta_gemm_prepared takes that format id back
+ * and computes out = fp16(s_w * s_a * (sign(W) (x) ternary(A))) exactly like bwta_gemm, with a
+ * kernel that reads that layout: the format id, not the path setting at the time of the second
+ * call, says how `prepared` is read, so changing the path in between is harmless.  An id that is
+ * neither of the two gives BWTA_ERR_UNSUPPORTED; passing the other layout's id reads the (other,
+ * possibly unwritten) region of the caller's own buffer, never memory outside it.  With planes and
+ * a shape the decode kernels do not cover, the product runs on the int8 matrix-core or popcount
+ * kernels (same bits), since no scratch comes with this call.  `prepared` is only read by it.
  */
+enum { BWTA_PREPARED_PLANES = 1, BWTA_PREPARED_FP4 = 2 };
 size_t bwta_prepared_bytes(int M, int K);
+int bwta_prepared_format(int M, int K);
 int bwta_prepare_act(const void *A, int64_t lda, const void *s_a, int a_scale_mode, int M, int K,
-                     void *prepared, size_t prepared_bytes, bwta_stream_t stream);
-int bwta_gemm_prepared(const void *prepared, size_t prepared_bytes, const uint32_t *wsign, int M,
-                       int N, int K, const void *s_a, int a_scale_mode, const void *s_w,
-                       int w_scale_mode, int32_t *acc, void *out, int64_t ldo,
+                     void *prepared, size_t prepared_bytes, int *prepared_format, bwta_stream_t stream);
+int bwta_gemm_prepared(const void *prepared, size_t prepared_bytes, int prepared_format,
+                       const uint32_t *wsign, int M, int N, int K, const void *s_a, int a_scale_mode,
+                       const void *s_w, int w_scale_mode, int32_t *acc, void *out, int64_t ldo,
                        bwta_stream_t stream);
 
 /*
@@ -208,15 +220,15 @@ int bwta_matmul_tt(const uint32_t *maskA, const uint32_t *signA, int64_t strideA
  *                                                     batch entry, entries strideA words apart
  *   out[b, m, n] = fp16( acc * fp32( alpha * (s_a * s_b) ) )   as bwta_matmul_tt
  * B is `preparedB`: what bwta_prepare_act wrote for the fp16 matrix [batch * N, K] that stacks the
- * batch entries' N rows (for Att V: V transposed, [heads * D, S]).  The boolean plane then plays the
+ * batch entries' N rows (for Att V: V transposed, [heads * D, S]), with the format id it reported.  The boolean plane then plays the
  * part the packed weights play in bwta_gemm_prepared, which is several times cheaper per product
  * than expanding both operands from planes (bwta_matmul_tt).  Same bits as bwta_matmul_tt.
- * Needs N a multiple of 128, the FP4 path (AUTO or BWTA_PATH_FP4, unchanged since the prepare
- * call) and batch * N > 128; BWTA_ERR_UNSUPPORTED otherwise.  out fp16 [batch][M][ldo], ldo >= N,
+ * Needs N a multiple of 128 and preparedB_format == BWTA_PREPARED_FP4 (which bwta_prepare_act
+ * chooses on the FP4 path, AUTO included, above 128 rows); BWTA_ERR_UNSUPPORTED otherwise.  out fp16 [batch][M][ldo], ldo >= N,
  * entries stride_out elements apart; s_a [batch, M] / s_b [batch, N] when VECTOR.
  */
 int bwta_matmul_bool_prepared(const uint32_t *maskA, int64_t strideA, const void *preparedB,
-                              size_t preparedB_bytes, int batch, int M, int N, int K, const void *s_a,
+                              size_t preparedB_bytes, int preparedB_format, int batch, int M, int N, int K, const void *s_a,
                               int a_scale_mode, const void *s_b, int b_scale_mode, float alpha,
                               void *out, int64_t ldo, int64_t stride_out, bwta_stream_t stream);
 
@@ -226,8 +238,10 @@ int bwta_matmul_bool_prepared(const uint32_t *maskA, int64_t strideA, const void
  * W is fp16 [N, ldw]; wsign is written in the layout of bwta_pack_weights; s_w is fp16 [N] (the
  * scale that minimises ||(W - mu) - s sign(W - mu)||^2; the printed (1/n)||W||_F is read as this
  * l1 mean).  Sums are exact (binary16 values are integers in units of 2^-24), so the planes equal
- * exact arithmetic bit for bit; the scale is rounded once from a double.  NaN / Inf entries stay
- * out of the mean and the scale (+Inf -> +1, -Inf and NaN -> -1).  K <= 32768.
+ * exact arithmetic bit for bit; the scale is rounded once from a double.  A NaN / Inf entry adds
+ * nothing to either sum, while both means still divide by K (mu_n = finite sum / K; s_w[n] = sum
+ * over the finite entries of |W - mu_n|, / K); its own bit is +Inf -> +1, -Inf and NaN -> -1.
+ * K <= 32768.
  */
 int bwta_prepare_weights(const void *W, int64_t ldw, int N, int K, uint32_t *wsign, void *s_w,
                          bwta_stream_t stream);
@@ -243,11 +257,12 @@ int bwta_act_scale(const void *A, int64_t lda, int M, int K, void *s, bwta_strea
  * bwta_act_scale and bwta_prepare_act in one pass over A (the single-pass form of the same
  * s_A^0 equation followed by the ternary function): writes s_a[m] = fp16(2 * mean_k |A[m, k]|)
  * (fp16 [M], the same bits as bwta_act_scale) and ternarises every token with its own scale into
- * `prepared` (see bwta_prepare_act; pass s_a with BWTA_SCALE_VECTOR to bwta_gemm_prepared).  A row
- * whose scale comes out 0 (all zeros or non-finite) ternarises to zero.  K <= 32768.
+ * `prepared`, reporting the layout in *prepared_format (see bwta_prepare_act; pass s_a with
+ * BWTA_SCALE_VECTOR to bwta_gemm_prepared).  A row whose scale comes out 0 (all zeros or
+ * non-finite) ternarises to zero.  K <= 32768.
  */
 int bwta_prepare_act_autoscale(const void *A, int64_t lda, int M, int K, void *s_a, void *prepared,
-                               size_t prepared_bytes, bwta_stream_t stream);
+                               size_t prepared_bytes, int *prepared_format, bwta_stream_t stream);
 
 /* Human-readable text for a return code (static storage). */
 const char *bwta_strerror(int code);
@@ -256,23 +271,6 @@ int bwta_last_hip_error(void);
 /* Select the contraction kernel family (process-wide).  Returns BWTA_OK or UNSUPPORTED. */
 int bwta_set_path(int path);
 int bwta_get_path(void);
-/* Which family AUTO resolves to for a shape: BWTA_PATH_POPC, BWTA_PATH_MFMA or BWTA_PATH_FP4. */
-int bwta_auto_path(int M, int N, int K);
-/* How many kernels bwta_linear launches for a shape under the current settings, given a dense
- * (lda = K), 16-byte-aligned fp16 input: 1 where ternarisation, product and epilogue run as one
- * kernel (short K), else 2.  Informational (benchmarks label their timings with it); 0 for a
- * non-positive dimension. */
-int bwta_linear_launches(int M, int N, int K);
-/* Tuning hook for benchmark sweeps: force the FP4 kernel's per-wavefront tile (22, 21, 12, 11, 13
- * = blocks of 32 rows x 32 columns per wavefront; 23 = 22 at three wavefronts per SIMD; 222 = 22
- * with K split over two groups of wavefronts), the popcount decode kernel's row split (1000 + 16 *
- * lanes per row (8, 16, 32) + chunks per lane; ignored where the registers cannot hold it) or the
- * matrix-core decode kernel's work split (2000 + 1024 * ring depth (2..4) + 64 * chunks per
- * wavefront (1..4) + tiles per workgroup (rounded up to a multiple of the ring depth, fewer if LDS
- * does not hold their partials)), or where bwta_linear runs as a single launch (900 never, 901
- * wherever the one-launch kernel can run, 900 + R the same with R channel splits per token
- * strip); 0 restores the built-in choices.  Results do not depend on it. */
-int bwta_set_tile(int tile);
 /* Library version, major * 100 + minor. */
 int bwta_version(void);
 

@@ -392,8 +392,9 @@ static uint16_t ratio_to_half(unsigned __int128 num, unsigned __int128 den)
  *   mu_n = mean_k W[n, k],  w[n, k] = sign(W[n, k] - mu_n),  s_w[n] = mean_k |W[n, k] - mu_n|
  * (the scale that minimises || (W - mu) - s sign(W - mu) ||^2; the printed (1/n)||W||_F is read as
  * this l1 mean).  All decisions are exact: binary16 values are integers in units of 2^-24, so
- * W[n,k] - mu_n >= 0 is the integer test K * W >= sum(W).  Non-finite entries do not enter the
- * mean or the scale; +Inf -> +1, -Inf and NaN -> -1.  w: int8 [N, K]; s_w: fp16 bits [N]. */
+ * W[n,k] - mu_n >= 0 is the integer test K * W >= sum(W).  A non-finite entry adds nothing
+ * to either sum while both means still divide by K (mu_n = finite sum / K, s_w[n] = sum over the
+ * finite entries of |W - mu_n|, / K); its own sign is +Inf -> +1, -Inf and NaN -> -1.  w: int8 [N, K]; s_w: fp16 bits [N]. */
 void bwta_oracle_prepare_weights(const uint16_t *W, int64_t ldw, int N, int K, int8_t *w, uint16_t *s_w)
 {
 #pragma omp parallel for schedule(static)

@@ -19,11 +19,13 @@ ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = -1, -2
 DTYPE_FP16, DTYPE_INT8 = 0, 1
 SCALE_NONE, SCALE_SCALAR, SCALE_VECTOR = 0, 1, 2
 PATH_AUTO, PATH_POPC, PATH_MFMA, PATH_FP4 = 0, 1, 2, 3
+PREPARED_PLANES, PREPARED_FP4 = 1, 2
+KERNEL_GEMV_POPC, KERNEL_GEMV_FP4, KERNEL_GEMM_FP4, KERNEL_GEMM_MFMA_I8, KERNEL_GEMM_POPC = 1, 2, 3, 4, 5
 
 EXPORTS = ["bwta_plane_row_words", "bwta_workspace_bytes", "bwta_quantize_pack_act",
            "bwta_pack_weights", "bwta_gemm", "bwta_linear", "bwta_strerror", "bwta_last_hip_error",
            "bwta_set_path", "bwta_get_path", "bwta_auto_path", "bwta_linear_launches", "bwta_version", "bwta_set_tile",
-           "bwta_prepared_bytes", "bwta_prepare_act", "bwta_gemm_prepared", "bwta_gemm_grouped",
+           "bwta_prepared_bytes", "bwta_prepared_format", "bwta_planned_kernel", "bwta_prepare_act", "bwta_gemm_prepared", "bwta_gemm_grouped",
            "bwta_quantize_pack_bool", "bwta_matmul_tt", "bwta_prepare_weights", "bwta_act_scale",
            "bwta_prepare_act_autoscale", "bwta_matmul_bool_prepared"]
 
@@ -53,10 +55,15 @@ _lib.bwta_linear.argtypes = [_P, _c.c_int64, _P, _c.c_int, _P, _P, _c.c_int, _c.
 _lib.bwta_prepared_bytes.restype = _c.c_size_t
 _lib.bwta_prepared_bytes.argtypes = [_c.c_int, _c.c_int]
 _lib.bwta_prepare_act.restype = _c.c_int
-_lib.bwta_prepare_act.argtypes = [_P, _c.c_int64, _P, _c.c_int, _c.c_int, _c.c_int, _P, _c.c_size_t, _P]
+_lib.bwta_planned_kernel.restype = _c.c_int
+_lib.bwta_planned_kernel.argtypes = [_c.c_int, _c.c_int, _c.c_int, _c.c_int]
+_lib.bwta_prepared_format.restype = _c.c_int
+_lib.bwta_prepared_format.argtypes = [_c.c_int, _c.c_int]
+_lib.bwta_prepare_act.argtypes = [_P, _c.c_int64, _P, _c.c_int, _c.c_int, _c.c_int, _P, _c.c_size_t,
+                                  _c.POINTER(_c.c_int), _P]
 _lib.bwta_gemm_prepared.restype = _c.c_int
-_lib.bwta_gemm_prepared.argtypes = [_P, _c.c_size_t, _P, _c.c_int, _c.c_int, _c.c_int, _P, _c.c_int, _P, _c.c_int,
-                                    _P, _P, _c.c_int64, _P]
+_lib.bwta_gemm_prepared.argtypes = [_P, _c.c_size_t, _c.c_int, _P, _c.c_int, _c.c_int, _c.c_int, _P, _c.c_int, _P,
+                                    _c.c_int, _P, _P, _c.c_int64, _P]
 
 
 class GemmProblem(_c.Structure):
@@ -77,9 +84,10 @@ _lib.bwta_act_scale.restype = _c.c_int
 _lib.bwta_act_scale.argtypes = [_P, _c.c_int64, _c.c_int, _c.c_int, _P, _P]
 _lib.bwta_prepare_act_autoscale.restype = _c.c_int
 _lib.bwta_matmul_bool_prepared.restype = _c.c_int
-_lib.bwta_matmul_bool_prepared.argtypes = [_P, _c.c_int64, _P, _c.c_size_t, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _P, _c.c_int,
+_lib.bwta_matmul_bool_prepared.argtypes = [_P, _c.c_int64, _P, _c.c_size_t, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _P, _c.c_int,
                                            _P, _c.c_int, _c.c_float, _P, _c.c_int64, _c.c_int64, _P]
-_lib.bwta_prepare_act_autoscale.argtypes = [_P, _c.c_int64, _c.c_int, _c.c_int, _P, _P, _c.c_size_t, _P]
+_lib.bwta_prepare_act_autoscale.argtypes = [_P, _c.c_int64, _c.c_int, _c.c_int, _P, _P, _c.c_size_t,
+                                            _c.POINTER(_c.c_int), _P]
 _lib.bwta_strerror.restype = _c.c_char_p
 _lib.bwta_strerror.argtypes = [_c.c_int]
 _lib.bwta_last_hip_error.restype = _c.c_int
@@ -253,34 +261,48 @@ def prepared_bytes(M, K):
     return int(_lib.bwta_prepared_bytes(M, K))
 
 
+def planned_kernel(operand, M, N, K):
+    return int(_lib.bwta_planned_kernel(operand, M, N, K))
+
+
+def prepared_format(M, K):
+    return int(_lib.bwta_prepared_format(M, K))
+
+
 def bwta_prepare_act(A, s_a, prepared, *, M, K, lda=None, a_scale_mode=None, prepared_bytes=None, stream=None):
+    """Returns the format id of what was written; hand it to the call that consumes `prepared`."""
     lda = K if lda is None else lda
+    fmt = _c.c_int(0)
     _check(_lib.bwta_prepare_act(_ptr(A), lda, _ptr(s_a), _mode(s_a, a_scale_mode), M, K, _ptr(prepared),
-                                 _nbytes(prepared, prepared_bytes), _stream(stream)))
+                                 _nbytes(prepared, prepared_bytes), _c.byref(fmt), _stream(stream)))
+    return fmt.value
 
 
 def bwta_prepare_act_autoscale(A, s_a, prepared, *, M, K, lda=None, prepared_bytes=None, stream=None):
+    """Returns the format id of what was written, as bwta_prepare_act."""
     lda = K if lda is None else lda
+    fmt = _c.c_int(0)
     _check(_lib.bwta_prepare_act_autoscale(_ptr(A), lda, M, K, _ptr(s_a), _ptr(prepared),
-                                           _nbytes(prepared, prepared_bytes), _stream(stream)))
+                                           _nbytes(prepared, prepared_bytes), _c.byref(fmt), _stream(stream)))
+    return fmt.value
 
 
-def bwta_matmul_bool_prepared(maskA, preparedB, s_a, s_b, out, *, batch, M, N, K, alpha=1.0, strideA=None, ldo=None,
+def bwta_matmul_bool_prepared(maskA, preparedB, s_a, s_b, out, *, fmt, batch, M, N, K, alpha=1.0, strideA=None, ldo=None,
                               stride_out=None, a_scale_mode=None, b_scale_mode=None, prepared_bytes=None, stream=None):
     rw = plane_row_words(K)
     strideA = M * rw if strideA is None else strideA
     ldo = N if ldo is None else ldo
     stride_out = M * ldo if stride_out is None else stride_out
     _check(_lib.bwta_matmul_bool_prepared(_ptr(maskA), strideA, _ptr(preparedB), _nbytes(preparedB, prepared_bytes),
-                                          batch, M, N, K, _ptr(s_a), _mode(s_a, a_scale_mode), _ptr(s_b),
+                                          fmt, batch, M, N, K, _ptr(s_a), _mode(s_a, a_scale_mode), _ptr(s_b),
                                           _mode(s_b, b_scale_mode), float(alpha), _ptr(out), ldo, stride_out,
                                           _stream(stream)))
 
 
-def bwta_gemm_prepared(prepared, wsign, s_a, s_w, acc, out, *, M, N, K, ldo=None, a_scale_mode=None,
+def bwta_gemm_prepared(prepared, wsign, s_a, s_w, acc, out, *, fmt, M, N, K, ldo=None, a_scale_mode=None,
                        w_scale_mode=None, prepared_bytes=None, stream=None):
     ldo = N if ldo is None else ldo
-    _check(_lib.bwta_gemm_prepared(_ptr(prepared), _nbytes(prepared, prepared_bytes), _ptr(wsign), M, N, K,
+    _check(_lib.bwta_gemm_prepared(_ptr(prepared), _nbytes(prepared, prepared_bytes), fmt, _ptr(wsign), M, N, K,
                                    _ptr(s_a), _mode(s_a, a_scale_mode), _ptr(s_w), _mode(s_w, w_scale_mode),
                                    _ptr(acc), _ptr(out), ldo, _stream(stream)))
 

@@ -1,6 +1,7 @@
 // C ABI of libbwta.so: host-side argument validation and dispatch.  Every check happens before
 // anything is enqueued, so a bad call never touches the device.
 #include "../../include/bwta.h"
+#include "../../include/bwta_tuning.h"
 
 #include <atomic>
 
@@ -43,18 +44,34 @@ bool fp4_uses_fragments(int M, int K)
     return resolve_path(M, 1, K) == BWTA_PATH_FP4 && !bwta::gemv_fp4_supported(g);
 }
 
+// Which kernel computes a product from canonical planes.  The tiled FP4 kernel is the only one that
+// needs scratch (it converts the planes into fragments first); when no scratch comes with the call
+// (have_scratch false: the operand was prepared as planes by an earlier call) a shape that would
+// take it runs on the int8 matrix-core kernel or the popcount kernels instead, which read planes
+// directly and give the same bits.
+int plan_from_planes(const bwta::GemmArgs &g, bool have_scratch)
+{
+    const int path = resolve_path(g.M, g.N, g.K);
+    if (path == BWTA_PATH_FP4 && bwta::gemv_fp4_supported(g)) return BWTA_KERNEL_GEMV_FP4;
+    if (path == BWTA_PATH_FP4 && have_scratch) return BWTA_KERNEL_GEMM_FP4;
+    if ((path == BWTA_PATH_MFMA || path == BWTA_PATH_FP4) && bwta::gemm_mfma_supported(g)) return BWTA_KERNEL_GEMM_MFMA_I8;
+    if (bwta::gemv_popc_supported(g)) return BWTA_KERNEL_GEMV_POPC;
+    return BWTA_KERNEL_GEMM_POPC;
+}
+
 // workspace layout: [mask planes | sign planes | FP4 activation fragments]
 int run_gemm(const bwta::GemmArgs &g, void *workspace, hipStream_t st)
 {
-    int path = resolve_path(g.M, g.N, g.K);
-    if (path == BWTA_PATH_FP4 && bwta::gemv_fp4_supported(g)) return hip_result(bwta::launch_gemv_fp4(g, st));
-    if (path == BWTA_PATH_FP4) {
+    switch (plan_from_planes(g, workspace != nullptr)) {
+    case BWTA_KERNEL_GEMV_FP4: return hip_result(bwta::launch_gemv_fp4(g, st));
+    case BWTA_KERNEL_GEMM_FP4: {
         uint32_t *frag = (uint32_t *)((char *)workspace + 2 * plane_bytes(g.M, g.K));
         return hip_result(bwta::launch_gemm_fp4(g, frag, false, st));
     }
-    if (path == BWTA_PATH_MFMA && bwta::gemm_mfma_supported(g)) return hip_result(bwta::launch_gemm_mfma(g, st));
-    if (bwta::gemv_popc_supported(g)) return hip_result(bwta::launch_gemv_popc(g, st));
-    return hip_result(bwta::launch_gemm_popc(g, st));
+    case BWTA_KERNEL_GEMM_MFMA_I8: return hip_result(bwta::launch_gemm_mfma(g, st));
+    case BWTA_KERNEL_GEMV_POPC: return hip_result(bwta::launch_gemv_popc(g, st));
+    default: return hip_result(bwta::launch_gemm_popc(g, st));
+    }
 }
 
 }  // namespace
@@ -163,10 +180,17 @@ int bwta_linear(const void *A, int64_t lda, const void *s_a, int a_scale_mode, c
         if (bwta::linear_fused_supported(A, lda, g))
             return hip_result(bwta::launch_linear_fused(A, lda, g, (hipStream_t)stream));
     }
-    rc = bwta_prepare_act(A, lda, s_a, a_scale_mode, M, K, workspace, workspace_bytes, stream);
+    int format = 0;
+    rc = bwta_prepare_act(A, lda, s_a, a_scale_mode, M, K, workspace, workspace_bytes, &format, stream);
     if (rc != BWTA_OK) return rc;
-    return bwta_gemm_prepared(workspace, workspace_bytes, wsign, M, N, K, s_a, a_scale_mode, s_w, w_scale_mode,
-                              nullptr, out, ldo, stream);
+    return bwta_gemm_prepared(workspace, workspace_bytes, format, wsign, M, N, K, s_a, a_scale_mode, s_w,
+                              w_scale_mode, nullptr, out, ldo, stream);
+}
+
+int bwta_prepared_format(int M, int K)
+{
+    if (M <= 0 || K <= 0) return BWTA_PREPARED_PLANES;
+    return fp4_uses_fragments(M, K) ? BWTA_PREPARED_FP4 : BWTA_PREPARED_PLANES;
 }
 
 size_t bwta_prepared_bytes(int M, int K)
@@ -176,10 +200,12 @@ size_t bwta_prepared_bytes(int M, int K)
 }
 
 int bwta_prepare_act(const void *A, int64_t lda, const void *s_a, int a_scale_mode, int M, int K,
-                     void *prepared, size_t prepared_bytes, bwta_stream_t stream)
+                     void *prepared, size_t prepared_bytes, int *prepared_format, bwta_stream_t stream)
 {
     if (!scale_mode_ok(a_scale_mode)) return BWTA_ERR_UNSUPPORTED;
     if (M < 0 || K < 0 || (M > 0 && K == 0)) return BWTA_ERR_SHAPE;
+    if (!prepared_format) return BWTA_ERR_NULL;
+    *prepared_format = bwta_prepared_format(M, K);  // decided once, here; the consumer is told, it does not re-derive it
     if (M == 0) return BWTA_OK;
     if (lda < K) return BWTA_ERR_SHAPE;
     if (!A) return BWTA_ERR_NULL;
@@ -189,7 +215,7 @@ int bwta_prepare_act(const void *A, int64_t lda, const void *s_a, int a_scale_mo
     if (!aligned(prepared, 256)) return BWTA_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
     bwta::ScaleArg sa{(const uint16_t *)s_a, s_a ? a_scale_mode : BWTA_SCALE_NONE};
-    if (fp4_uses_fragments(M, K)) {
+    if (*prepared_format == BWTA_PREPARED_FP4) {
         uint32_t *frag = (uint32_t *)((char *)prepared + 2 * plane_bytes(M, K));
         return hip_result(bwta::launch_quantize_to_fp4(A, lda, sa, M, K, frag, st));
     }
@@ -199,9 +225,11 @@ int bwta_prepare_act(const void *A, int64_t lda, const void *s_a, int a_scale_mo
 }
 
 int bwta_prepare_act_autoscale(const void *A, int64_t lda, int M, int K, void *s_a, void *prepared,
-                               size_t prepared_bytes, bwta_stream_t stream)
+                               size_t prepared_bytes, int *prepared_format, bwta_stream_t stream)
 {
     if (M < 0 || K < 0 || (M > 0 && K == 0)) return BWTA_ERR_SHAPE;
+    if (!prepared_format) return BWTA_ERR_NULL;
+    *prepared_format = bwta_prepared_format(M, K);
     if (M == 0) return BWTA_OK;
     if (lda < K) return BWTA_ERR_SHAPE;
     if (K > 32768) return BWTA_ERR_UNSUPPORTED;  // a token row is held in one workgroup's registers
@@ -212,16 +240,18 @@ int bwta_prepare_act_autoscale(const void *A, int64_t lda, int M, int K, void *s
     hipStream_t st = (hipStream_t)stream;
     uint32_t *mask = (uint32_t *)prepared;
     uint32_t *sign = (uint32_t *)((char *)prepared + plane_bytes(M, K));
-    uint32_t *frag = fp4_uses_fragments(M, K) ? (uint32_t *)((char *)prepared + 2 * plane_bytes(M, K)) : nullptr;
+    uint32_t *frag =
+        *prepared_format == BWTA_PREPARED_FP4 ? (uint32_t *)((char *)prepared + 2 * plane_bytes(M, K)) : nullptr;
     return hip_result(bwta::launch_act_scale_quantize(A, lda, M, K, (uint16_t *)s_a, frag, mask, sign, st));
 }
 
-int bwta_gemm_prepared(const void *prepared, size_t prepared_bytes, const uint32_t *wsign, int M, int N, int K,
-                       const void *s_a, int a_scale_mode, const void *s_w, int w_scale_mode, int32_t *acc,
-                       void *out, int64_t ldo, bwta_stream_t stream)
+int bwta_gemm_prepared(const void *prepared, size_t prepared_bytes, int prepared_format, const uint32_t *wsign,
+                       int M, int N, int K, const void *s_a, int a_scale_mode, const void *s_w, int w_scale_mode,
+                       int32_t *acc, void *out, int64_t ldo, bwta_stream_t stream)
 {
     int rc = check_gemm_common(M, N, K, s_a, a_scale_mode, s_w, w_scale_mode, out, ldo);
     if (rc != BWTA_OK) return rc;
+    if (prepared_format != BWTA_PREPARED_PLANES && prepared_format != BWTA_PREPARED_FP4) return BWTA_ERR_UNSUPPORTED;
     if (M == 0 || N == 0) return BWTA_OK;
     if (!wsign) return BWTA_ERR_NULL;
     if (!acc && !out) return BWTA_ERR_NULL;
@@ -235,7 +265,9 @@ int bwta_gemm_prepared(const void *prepared, size_t prepared_bytes, const uint32
                      {(const uint16_t *)s_a, s_a ? a_scale_mode : BWTA_SCALE_NONE},
                      {(const uint16_t *)s_w, s_w ? w_scale_mode : BWTA_SCALE_NONE},
                      acc, (uint16_t *)out, ldo};
-    if (fp4_uses_fragments(M, K)) {
+    // The operand's format, not the current path setting, says which kernels can read it: fragments go
+    // to the tiled FP4 kernel; planes go to a kernel that reads planes and needs no scratch.
+    if (prepared_format == BWTA_PREPARED_FP4) {
         uint32_t *frag = (uint32_t *)((char *)prepared + 2 * plane_bytes(M, K));
         return hip_result(bwta::launch_gemm_fp4(g, frag, true, st));
     }
@@ -333,7 +365,7 @@ int bwta_matmul_tt(const uint32_t *maskA, const uint32_t *signA, int64_t strideA
 }
 
 int bwta_matmul_bool_prepared(const uint32_t *maskA, int64_t strideA, const void *preparedB, size_t preparedB_bytes,
-                              int batch, int M, int N, int K, const void *s_a, int a_scale_mode, const void *s_b,
+                              int preparedB_format, int batch, int M, int N, int K, const void *s_a, int a_scale_mode, const void *s_b,
                               int b_scale_mode, float alpha, void *out, int64_t ldo, int64_t stride_out,
                               bwta_stream_t stream)
 {
@@ -348,7 +380,7 @@ int bwta_matmul_bool_prepared(const uint32_t *maskA, int64_t strideA, const void
     // must hold matrix-core fragments, which bwta_prepare_act writes on the FP4 path above 128 rows.
     if ((N & 127) != 0 || (int64_t)batch * N > 0x7fffffff) return BWTA_ERR_UNSUPPORTED;
     const int rows_b = batch * N;
-    if (!fp4_uses_fragments(rows_b, K)) return BWTA_ERR_UNSUPPORTED;
+    if (preparedB_format != BWTA_PREPARED_FP4) return BWTA_ERR_UNSUPPORTED;
     const int64_t rw = bwta_plane_row_words(K);
     if (batch > 1 && strideA < (int64_t)M * rw) return BWTA_ERR_SHAPE;
     if (batch > 1 && stride_out < (int64_t)(M - 1) * ldo + N) return BWTA_ERR_SHAPE;
@@ -435,7 +467,18 @@ int bwta_linear_launches(int M, int N, int K)
     return bwta::linear_fused_supported(dense, K, g) ? 1 : 2;
 }
 
-int bwta_version(void) { return 1; }
+int bwta_planned_kernel(int operand, int M, int N, int K)
+{
+    if (M <= 0 || N <= 0 || K <= 0) return 0;
+    if (operand == BWTA_PREPARED_FP4) return BWTA_KERNEL_GEMM_FP4;
+    if (operand != 0 && operand != BWTA_PREPARED_PLANES) return 0;
+    bwta::GemmArgs g{};
+    g.M = M, g.N = N, g.K = K;
+    g.rw = (int)bwta_plane_row_words(K);
+    return plan_from_planes(g, operand == 0);
+}
+
+int bwta_version(void) { return 2; }
 
 int bwta_set_tile(int tile)
 {

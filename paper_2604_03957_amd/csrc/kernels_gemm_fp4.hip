@@ -18,6 +18,7 @@
 //
 // Kernels here: k_planes_to_fp4 / k_quantize_to_fp4 (bit planes / fp16 activations -> fragments),
 // k_gemm_fp4 (the tiled product) and k_linear_fused (ternarise + product in one launch, short K).
+#include <atomic>
 #include <type_traits>
 
 #include "bwta_internal.h"
@@ -723,8 +724,10 @@ __global__ __launch_bounds__(64 * NWV) void k_linear_fused(const uint16_t *__res
     }
 }
 
-static int g_linear_fused = 1;  // 0: never; 1: where it pays; 2: wherever it can run; g_linear_fused_r > 0 forces the channel splits
-static int g_linear_fused_r = 0;
+// tuning settings: process-wide, read once per launch decision (relaxed atomics: any thread may set
+// them while others launch; a launch sees either the old or the new value)
+static std::atomic<int> g_linear_fused{1};  // 0: never; 1: where it pays; 2: wherever it can run; g_linear_fused_r > 0 forces the channel splits
+static std::atomic<int> g_linear_fused_r{0};
 
 }  // namespace
 
@@ -763,9 +766,10 @@ hipError_t launch_quantize_to_fp4(const void *A, int64_t lda, ScaleArg s_a, int 
 // up to N = 4096 and M = 8192; beyond, the two kernels win.
 bool linear_fused_supported(const void *A, int64_t lda, const GemmArgs &g)
 {
-    if (g_linear_fused == 0) return false;
+    const int mode = g_linear_fused.load(std::memory_order_relaxed);
+    if (mode == 0) return false;
     const bool pays = g.K <= 768 || (g.N <= 4096 && g.M <= 8192);
-    return (pays || g_linear_fused == 2) && g.K <= 1024 && g.N >= 128 && g.out != nullptr &&
+    return (pays || mode == 2) && g.K <= 1024 && g.N >= 128 && g.out != nullptr &&
            g.acc == nullptr && ((uintptr_t)A % 16) == 0 && (lda % 8) == 0 && (g.K % 8) == 0;
 }
 
@@ -780,7 +784,8 @@ hipError_t launch_linear_fused(const void *A, int64_t lda, const GemmArgs &g, hi
     // with several groups per wavefront the next group's weight bits arrive, and the other
     // wavefronts' MFMAs run, while a group is scaled and stored (groups of 4 were 1 us slower).
     int R = (256 + nstrips - 1) / nstrips;
-    if (g_linear_fused_r > 0) R = g_linear_fused_r;
+    const int forced_r = g_linear_fused_r.load(std::memory_order_relaxed);
+    if (forced_r > 0) R = forced_r;
     if (R > ncb) R = ncb;
     const int NWV = (ncb + R - 1) / R >= 8 ? 8 : 4;
     if (R < (ncb + 63) / 64) R = (ncb + 63) / 64;
@@ -808,8 +813,8 @@ hipError_t launch_linear_fused(const void *A, int64_t lda, const GemmArgs &g, hi
 
 void set_linear_fused(int mode, int r)
 {
-    g_linear_fused = mode;
-    g_linear_fused_r = r;
+    g_linear_fused.store(mode, std::memory_order_relaxed);
+    g_linear_fused_r.store(r, std::memory_order_relaxed);
 }
 
 // BWTA_Att with V^T prepared as fragments.  g: M = rows of V^T per batch entry (a multiple of 128),
@@ -823,8 +828,8 @@ hipError_t launch_att_v_fp4(const GemmArgs &g, const uint32_t *frag, int batch, 
     return launch<2, 2, 2, 2, 2, false, 1, 8, 1>(g, frag, s_pad, st, batch, ba);
 }
 
-static int g_fp4_tile = 0;
-void set_fp4_tile(int t) { g_fp4_tile = t; }
+static std::atomic<int> g_fp4_tile{0};
+void set_fp4_tile(int t) { g_fp4_tile.store(t, std::memory_order_relaxed); }
 
 // frag_ready: the fragments were already produced by launch_quantize_to_fp4 (planes unused)
 hipError_t launch_gemm_fp4(const GemmArgs &g, uint32_t *frag, bool frag_ready, hipStream_t st)
@@ -845,7 +850,7 @@ hipError_t launch_gemm_fp4(const GemmArgs &g, uint32_t *frag, bool frag_ready, h
         if (e != hipSuccess) return e;
     }
     if (g.acc) return launch<2, 2, 2, 2, 2, true>(g, frag, s_pad, st);  // int32 output: test / debug path
-    switch (g_fp4_tile) {  // forced tile (tuning sweeps); 0 = heuristic below
+    switch (g_fp4_tile.load(std::memory_order_relaxed)) {  // forced tile (tuning sweeps); 0 = heuristic below
     case 22: return launch<2, 2, 2, 2, 2, false>(g, frag, s_pad, st);
     case 23: return launch<2, 2, 2, 2, 3, false>(g, frag, s_pad, st);
     case 21: return launch<2, 1, 2, 2, 3, false>(g, frag, s_pad, st);

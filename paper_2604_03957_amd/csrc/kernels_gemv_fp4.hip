@@ -35,6 +35,8 @@
 // the E2M1 codes 0.5, 1, 2 and a sign; tokens carrying -4 t, -2 t, -t, +t; a per-token correction
 // starting the accumulators) cuts the expansion from 7 to 4 operations per word and is exact, but
 // the kernel is not bound by the vector ALU: no faster, and the extra registers cost occupancy.
+#include <atomic>
+
 #include "bwta_internal.h"
 
 namespace bwta {
@@ -311,7 +313,7 @@ __global__ __launch_bounds__(64 * MAXW, MAXW == 4 && RPW <= 2 ? 5 : 4) void k_ge
     }
 }
 
-int g_force_rpw = 0, g_force_t = 0, g_force_pf = 0;  // tuning override
+std::atomic<int> g_force_rpw{0}, g_force_t{0}, g_force_pf{0};  // tuning override (relaxed: a launch sees old or new)
 
 size_t decode_lds_bytes(int RPW, int KW, int T)
 {
@@ -355,10 +357,12 @@ hipError_t launch_shape(const DecodeBatch &b, int count, DecodeShape sh, hipStre
     // (a single small matrix: one tile per workgroup, so that every compute unit gets one)
     int T = work >= 8 * 1024 ? 8 : work >= 4 * 1024 ? 4 : work >= 1024 ? 2 : 1;
     int PF = T == 1 ? 1 : RPW >= 3 ? 2 : T >= 4 ? 4 : 2;
-    if (g_force_rpw) {
-        if ((chunks + g_force_rpw - 1) / g_force_rpw <= 16) RPW = g_force_rpw;
-        if (g_force_t) T = g_force_t;
-        if (g_force_pf) PF = g_force_pf;
+    const int f_rpw = g_force_rpw.load(std::memory_order_relaxed), f_t = g_force_t.load(std::memory_order_relaxed),
+              f_pf = g_force_pf.load(std::memory_order_relaxed);
+    if (f_rpw) {
+        if ((chunks + f_rpw - 1) / f_rpw <= 16) RPW = f_rpw;
+        if (f_t) T = f_t;
+        if (f_pf) PF = f_pf;
     }
     const int KW = (chunks + RPW - 1) / RPW;
     T = (T + PF - 1) / PF * PF;
@@ -408,7 +412,13 @@ hipError_t launch_gemv_fp4_grouped(const GemmArgs *gs, int count, hipStream_t st
             b.out[i] = g.out;
         }
         const int P = g0.rw / 4;
-        DecodeShape sh{g0.M, g0.N, g0.rw, g0.s_a.mode, g0.s_w.mode, P, 0, 1, g0.ldo};
+        // the call's scale modes: those of any problem that has the scale (one without reads as 1)
+        int a_mode = 0, w_mode = 0;
+        for (int i = 0; i < n; ++i) {
+            if (gs[base + i].s_a.mode) a_mode = gs[base + i].s_a.mode;
+            if (gs[base + i].s_w.mode) w_mode = gs[base + i].s_w.mode;
+        }
+        DecodeShape sh{g0.M, g0.N, g0.rw, a_mode, w_mode, P, 0, 1, g0.ldo};
         hipError_t e = launch_shape(b, n, sh, st);
         if (e != hipSuccess) return e;
     }
@@ -419,9 +429,9 @@ hipError_t launch_gemv_fp4(const GemmArgs &g, hipStream_t st) { return launch_ge
 
 void set_gemv_fp4_tile(int rpw, int t, int pf)
 {
-    g_force_rpw = rpw;
-    g_force_t = t;
-    g_force_pf = (pf >= 1 && pf <= 4) ? pf : 0;
+    g_force_rpw.store(rpw, std::memory_order_relaxed);
+    g_force_t.store(t, std::memory_order_relaxed);
+    g_force_pf.store((pf >= 1 && pf <= 4) ? pf : 0, std::memory_order_relaxed);
 }
 
 }  // namespace bwta

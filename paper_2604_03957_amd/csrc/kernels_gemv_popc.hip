@@ -8,6 +8,8 @@
 // Lane partial counts are summed across the group with DPP adds, then the group's lanes write one
 // token each.  One launch can walk several problems of the same shape (grid.y), which is how a
 // decode step's independent matrices (or a bandwidth measurement) share one dispatch.
+#include <atomic>
+
 #include "bwta_internal.h"
 
 namespace bwta {
@@ -214,14 +216,15 @@ hipError_t launch_t(const GemvBatch &b, int count, const GemvShape &sh, hipStrea
     return hipGetLastError();
 }
 
-int g_force_g = 0, g_force_nch = 0;  // tuning override (bwta_set_tile)
+std::atomic<int> g_force_g{0}, g_force_nch{0};  // tuning override (bwta_set_tile; relaxed: a launch sees old or new)
 
 template <int MT>
 hipError_t launch_m(const GemvBatch &b, int count, const GemvShape &sh, hipStream_t st)
 {
+    const int f_g = g_force_g.load(std::memory_order_relaxed), f_nch = g_force_nch.load(std::memory_order_relaxed);
 #define BWTA_GEMV_FORCE(G_, NCH_)                                                                  \
     if constexpr (MT * NCH_ <= 16) {                                                               \
-        if (g_force_g == G_ && g_force_nch == NCH_ && sh.C4 <= G_ * NCH_)                          \
+        if (f_g == G_ && f_nch == NCH_ && sh.C4 <= G_ * NCH_)                                      \
             return launch_t<MT, G_, NCH_>(b, count, sh, st);                                       \
     }
     BWTA_GEMV_FORCE(8, 4) BWTA_GEMV_FORCE(16, 2) BWTA_GEMV_FORCE(32, 1) BWTA_GEMV_FORCE(16, 6)
@@ -285,7 +288,13 @@ hipError_t launch_gemv_popc_grouped(const GemmArgs *gs, int count, hipStream_t s
                 b.acc[i] = g.acc ? g.acc + (int64_t)m0 * g.N : nullptr;
                 b.out[i] = g.out ? g.out + (int64_t)m0 * g.ldo : nullptr;
             }
-            GemvShape sh{mt, g0.N, g0.rw, g0.rw / 4, g0.s_a.mode, g0.s_w.mode, g0.ldo};
+            // the call's scale modes: those of any problem that has the scale (one without reads as 1)
+            int a_mode = 0, w_mode = 0;
+            for (int i = 0; i < n; ++i) {
+                if (gs[base + i].s_a.mode) a_mode = gs[base + i].s_a.mode;
+                if (gs[base + i].s_w.mode) w_mode = gs[base + i].s_w.mode;
+            }
+            GemvShape sh{mt, g0.N, g0.rw, g0.rw / 4, a_mode, w_mode, g0.ldo};
             hipError_t e = launch_any(b, n, sh, st);
             if (e != hipSuccess) return e;
         }
@@ -297,8 +306,8 @@ hipError_t launch_gemv_popc(const GemmArgs &g, hipStream_t st) { return launch_g
 
 void set_gemv_tile(int g, int nch)
 {
-    g_force_g = g;
-    g_force_nch = nch;
+    g_force_g.store(g, std::memory_order_relaxed);
+    g_force_nch.store(nch, std::memory_order_relaxed);
 }
 
 }  // namespace bwta

@@ -1,6 +1,6 @@
 """Seeded synthetic inputs shaped like the paper's transformer workloads.
 
-This module only *draws numbers*: a counter-based generator (SplitMix64 finaliser
+This module (outside the product package and outside the oracle) only *draws numbers*: a counter-based generator (SplitMix64 finaliser
 over seed, tensor id and element index) turned into uniform, Gaussian, Laplace,
 ternary and +-1 tensors.  It holds none of the method's arithmetic (no
 ternarisation, packing, product or epilogue) and imports neither the oracle nor
@@ -97,14 +97,6 @@ def laplace_activations(seed, tensor_id, M, K):
     return laplace(seed, tensor_id, M * K).reshape(M, K).astype(np.float16)
 
 
-def token_scales_l1(A):
-    """Per-token activation scale handed to the layer as an input.  At inference the
-    scale is a trained parameter; the synthetic stand-in is the value training starts
-    from, twice the mean absolute activation of the token, rounded to fp16."""
-    a = A.astype(np.float64)
-    return (2.0 * np.mean(np.abs(a), axis=1)).astype(np.float16)
-
-
 # ---- the five benchmark configurations -------------------------------------------------
 
 def config1():
@@ -121,12 +113,16 @@ DECODE_SHAPES = {"upgate": (4096, 11008), "down": (11008, 4096)}
 
 
 def config2(which, M=4096):
-    """Encoder FFN: fp16 activations with outlier channels, full path."""
+    """Encoder FFN: fp16 activations with outlier channels, full path.  The per-token activation
+    scale is an input of the layer too (at inference a trained parameter; the synthetic stand-in
+    is the value training starts it from), but deriving it from A is the method's arithmetic, so
+    it is not computed here: each side's harness derives `s_a` from A with its own
+    implementation of that statistic (the oracle's in tests, the library's in the benchmark)."""
     seed = 1
     K, N = FFN_SHAPES[which]
     tid = 10 if which == "up" else 20
     A = gaussian_outlier_activations(seed, tid + 1, M, K)
-    return dict(name="c2_ffn_" + which, M=M, N=N, K=K, A=A, s_a=token_scales_l1(A),
+    return dict(name="c2_ffn_" + which, M=M, N=N, K=K, A=A,
                 w=binary_pm1(seed, tid + 2, (N, K)), s_w=scales(seed, tid + 3, N))
 
 

@@ -12,9 +12,12 @@ FAKE = 0x7F0000001000  # a well-aligned, never dereferenced "device" address
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "bwta.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(bwta_[a-z0-9_]+)\s*\(", text)))
+    names = set()
+    for header in ("bwta.h", "bwta_tuning.h"):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(bwta_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported():
@@ -114,12 +117,47 @@ def test_prepare_and_gemm_prepared_reject_bad_arguments():
     assert _code(B.bwta_prepare_act, FAKE, FAKE, FAKE, **dict(kw, prepared_bytes=pb - 1)) == B.ERR_WORKSPACE
     assert _code(B.bwta_prepare_act, FAKE, FAKE, FAKE + 32, **kw) == B.ERR_ALIGN
     assert _code(B.bwta_prepare_act, FAKE, FAKE, FAKE, **dict(kw, lda=64)) == B.ERR_SHAPE
-    kw = dict(M=8, N=8, K=128, stream=0, a_scale_mode=B.SCALE_VECTOR, w_scale_mode=B.SCALE_VECTOR, prepared_bytes=pb)
+    kw = dict(M=8, N=8, K=128, stream=0, a_scale_mode=B.SCALE_VECTOR, w_scale_mode=B.SCALE_VECTOR, prepared_bytes=pb,
+              fmt=B.PREPARED_PLANES)
     g = B.bwta_gemm_prepared
     assert _code(g, None, FAKE, FAKE, FAKE, None, FAKE, **kw) == B.ERR_WORKSPACE
     assert _code(g, FAKE, None, FAKE, FAKE, None, FAKE, **kw) == B.ERR_NULL
     assert _code(g, FAKE, FAKE, FAKE, FAKE, None, None, **kw) == B.ERR_NULL
     assert _code(g, FAKE, FAKE, FAKE, FAKE, None, FAKE, **dict(kw, ldo=4)) == B.ERR_SHAPE
+    # the operand's format travels with it: an id that names neither layout is refused before any launch
+    for bad in (0, 3, -1, 77):
+        assert _code(g, FAKE, FAKE, FAKE, FAKE, None, FAKE, **dict(kw, fmt=bad)) == B.ERR_UNSUPPORTED
+
+
+def test_prepared_format_and_planned_kernel():
+    """What bwta_prepare_act writes is decided once and reported; the consumer's kernel follows from
+    that id and the shape, never from a second look at the path setting.  In particular prepared
+    planes never resolve to the tiled FP4 kernel, which would need scratch the call does not have:
+    that includes a decode-sized token count against a packed matrix too large for the decode
+    kernel's 32-bit offsets (the shape that used to fall through to it)."""
+    assert B.prepared_format(2048, 4096) == B.PREPARED_FP4 and B.prepared_format(16, 4096) == B.PREPARED_PLANES
+    assert B.prepared_format(128, 11008) == B.PREPARED_PLANES and B.prepared_format(129, 11008) == B.PREPARED_FP4
+    assert B.planned_kernel(B.PREPARED_FP4, 2048, 4096, 4096) == B.KERNEL_GEMM_FP4
+    assert B.planned_kernel(B.PREPARED_PLANES, 16, 11008, 4096) == B.KERNEL_GEMV_FP4
+    assert B.planned_kernel(0, 2048, 4096, 4096) == B.KERNEL_GEMM_FP4
+    assert B.planned_kernel(0, 1, 4096, 4096) == B.KERNEL_GEMV_POPC
+    huge_n = (1 << 32) // (344 * 4) + 1                       # (N + 4096) * row bytes no longer fits 32 bits
+    for M in (2, 16, 128):
+        assert B.planned_kernel(0, M, huge_n, 11008) == B.KERNEL_GEMM_FP4          # with a workspace: tiled kernel
+        k = B.planned_kernel(B.PREPARED_PLANES, M, huge_n, 11008)
+        assert k in (B.KERNEL_GEMM_MFMA_I8, B.KERNEL_GEMM_POPC, B.KERNEL_GEMV_POPC), k
+    # prepared planes under every path setting, over a grid of shapes: never the kernel that needs scratch
+    try:
+        for path in (B.PATH_AUTO, B.PATH_POPC, B.PATH_MFMA, B.PATH_FP4):
+            B.set_path(path)
+            for M in (1, 2, 16, 128, 129, 2048):
+                for N in (1, 128, 4096, huge_n):
+                    for K in (32, 1024, 4096, 11008, 30000):
+                        assert B.planned_kernel(B.PREPARED_PLANES, M, N, K) not in (0, B.KERNEL_GEMM_FP4)
+                        assert B.planned_kernel(B.PREPARED_FP4, M, N, K) == B.KERNEL_GEMM_FP4
+    finally:
+        B.set_path(B.PATH_AUTO)
+    assert B.planned_kernel(5, 8, 8, 8) == 0 and B.planned_kernel(0, 0, 8, 8) == 0
 
 
 def test_attention_entry_points_reject_bad_arguments():
@@ -174,7 +212,7 @@ def test_weight_preparation_entry_points_reject_bad_arguments():
 
 def test_prepared_attention_product_rejects_bad_arguments():
     f = B.bwta_matmul_bool_prepared
-    kw = dict(batch=2, M=64, N=128, K=256, stream=0, prepared_bytes=B.prepared_bytes(256, 256))
+    kw = dict(batch=2, M=64, N=128, K=256, stream=0, prepared_bytes=B.prepared_bytes(256, 256), fmt=B.PREPARED_FP4)
     assert _code(f, None, FAKE, None, None, FAKE, **kw) == B.ERR_NULL
     assert _code(f, FAKE, FAKE, None, None, None, **kw) == B.ERR_NULL
     assert _code(f, FAKE, None, None, None, FAKE, **kw) == B.ERR_WORKSPACE
@@ -183,7 +221,8 @@ def test_prepared_attention_product_rejects_bad_arguments():
     assert _code(f, FAKE + 4, FAKE, None, None, FAKE, **kw) == B.ERR_ALIGN
     assert _code(f, FAKE, FAKE, None, None, FAKE, **dict(kw, strideA=64 * 8 + 2)) == B.ERR_ALIGN
     assert _code(f, FAKE, FAKE, None, None, FAKE, **dict(kw, N=96)) == B.ERR_UNSUPPORTED      # not a multiple of 128
-    assert _code(f, FAKE, FAKE, None, None, FAKE, **dict(kw, batch=1)) == B.ERR_UNSUPPORTED   # 128 rows: no fragments
+    assert _code(f, FAKE, FAKE, None, None, FAKE, **dict(kw, fmt=B.PREPARED_PLANES)) == B.ERR_UNSUPPORTED  # needs fragments
+    assert _code(f, FAKE, FAKE, None, None, FAKE, **dict(kw, fmt=0)) == B.ERR_UNSUPPORTED
     assert _code(f, FAKE, FAKE, None, None, FAKE, **dict(kw, alpha=float("nan"))) == B.ERR_UNSUPPORTED
     assert _code(f, FAKE, FAKE, None, None, FAKE, **dict(kw, ldo=64)) == B.ERR_SHAPE
     assert _code(f, FAKE, FAKE, None, None, FAKE, **dict(kw, strideA=8)) == B.ERR_SHAPE

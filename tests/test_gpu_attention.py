@@ -10,7 +10,7 @@ import torch
 import oracle
 from gpu_util import dev, host_u32, max_rel_err, same_half
 from paper_2604_03957_amd import binding as B
-from paper_2604_03957_amd import synth
+import synth
 
 pytestmark = pytest.mark.gpu
 RTOL = 1e-3
@@ -213,8 +213,8 @@ def test_att_v_with_v_prepared_once(batch, M, N, K, vec):
     prep = torch.empty(B.prepared_bytes(batch * N, K), dtype=torch.uint8, device=DEV)
     stride_out = M * ldo + pad_out
     out = torch.full((batch * stride_out,), float("nan"), dtype=torch.float16, device=DEV)
-    B.bwta_prepare_act(dev(v16), None, prep, M=batch * N, K=K)
-    B.bwta_matmul_bool_prepared(dev(ma), prep, dev(s_a), dev(s_b), out, batch=batch, M=M, N=N, K=K, alpha=alpha,
+    fmt = B.bwta_prepare_act(dev(v16), None, prep, M=batch * N, K=K)
+    B.bwta_matmul_bool_prepared(dev(ma), prep, dev(s_a), dev(s_b), out, fmt=fmt, batch=batch, M=M, N=N, K=K, alpha=alpha,
                                 strideA=M * rw + pad_a, ldo=ldo, stride_out=stride_out)
     torch.cuda.synchronize()
     out = out.cpu().numpy()

@@ -8,7 +8,8 @@ import torch
 import oracle
 from gpu_util import dev, gpu_pack_weights, same_half, workspace
 from paper_2604_03957_amd import binding as B
-from paper_2604_03957_amd import synth
+import inputs
+import synth
 
 pytestmark = pytest.mark.gpu
 
@@ -22,7 +23,7 @@ def _rows(M, seed):
 
 @pytest.mark.parametrize("which", ["up", "down"])
 def test_config2_ffn_full_path_sampled_rows(which):
-    c = synth.config2(which)
+    c = inputs.config2(which)
     M, N, K = c["M"], c["N"], c["K"]
     print("config2", which, M, N, K, flush=True)
     wsign = gpu_pack_weights(c["w"])
@@ -92,7 +93,7 @@ def test_config5_block_linears_sampled_rows(name, K, N):
     seed, M = 4, 2048
     print("config5", name, M, N, K, flush=True)
     x = synth.laplace_activations(seed, 100 + K % 97, M, K)
-    s_a = synth.token_scales_l1(x)
+    s_a = oracle.act_scale(x)
     w = synth.binary_pm1(seed, 200 + N % 89, (N, K))
     s_w = synth.scales(seed, 300, N)
     prep = torch.empty(B.prepared_bytes(M, K), dtype=torch.uint8, device="cuda:0")

@@ -10,7 +10,7 @@ import torch
 import oracle
 from gpu_util import dev, gpu_pack_weights, same_half
 from paper_2604_03957_amd import binding as B
-from paper_2604_03957_amd import synth
+import synth
 
 pytestmark = pytest.mark.gpu
 
@@ -133,8 +133,8 @@ def test_row_kernels_every_group_count(K):
         prep = torch.empty(B.prepared_bytes(M, K), dtype=torch.uint8, device="cuda:0")
         s2 = torch.zeros(M, dtype=torch.float16, device="cuda:0")
         out = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda:0")
-        B.bwta_prepare_act_autoscale(dev(A), s2, prep, M=M, K=K)
-        B.bwta_gemm_prepared(prep, gpu_pack_weights(w), s2, dev(s_w), None, out, M=M, N=N, K=K)
+        fmt = B.bwta_prepare_act_autoscale(dev(A), s2, prep, M=M, K=K)
+        B.bwta_gemm_prepared(prep, gpu_pack_weights(w), s2, dev(s_w), None, out, fmt=fmt, M=M, N=N, K=K)
         torch.cuda.synchronize()
         assert np.array_equal(s2.cpu().numpy().view(np.uint16), want_s.view(np.uint16))
         assert same_half(out.cpu().numpy(), want)

@@ -10,7 +10,7 @@ import torch
 import oracle
 from gpu_util import DEV, dev, gpu_pack_weights, workspace
 from paper_2604_03957_amd import binding as B
-from paper_2604_03957_amd import synth
+import synth
 
 pytestmark = pytest.mark.gpu
 
@@ -36,7 +36,7 @@ def test_ternarise_more_than_2g_input_elements():
     assert M * K > 2**31
     print("tall input", M, K, flush=True)
     base = synth.gaussian_outlier_activations(21, 0, PERIOD, K)
-    s_base = synth.token_scales_l1(base)
+    s_base = oracle.act_scale(base)
     w = synth.binary_pm1(21, 1, (N, K))
     s_w = synth.scales(21, 2, N)
     t = oracle.ternarize(base, s_base)
@@ -61,16 +61,16 @@ def test_ternarise_more_than_2g_input_elements():
     prepared = torch.empty(B.prepared_bytes(M, K), dtype=torch.uint8, device=DEV)
     wsign = gpu_pack_weights(w)
     out = torch.full((M, N), float("nan"), dtype=torch.float16, device=DEV)
-    B.bwta_prepare_act(A, s_a, prepared, M=M, K=K)
-    B.bwta_gemm_prepared(prepared, wsign, s_a, dev(s_w), None, out, M=M, N=N, K=K)
+    fmt = B.bwta_prepare_act(A, s_a, prepared, M=M, K=K)
+    B.bwta_gemm_prepared(prepared, wsign, s_a, dev(s_w), None, out, fmt=fmt, M=M, N=N, K=K)
     torch.cuda.synchronize()
     assert _same_rows(out, dev(out_b), idx)
 
     # and with the token scales computed in the same pass
     s_got = torch.zeros(M, dtype=torch.float16, device=DEV)
     out.fill_(float("nan"))
-    B.bwta_prepare_act_autoscale(A, s_got, prepared, M=M, K=K)
-    B.bwta_gemm_prepared(prepared, wsign, s_got, dev(s_w), None, out, M=M, N=N, K=K)
+    fmt = B.bwta_prepare_act_autoscale(A, s_got, prepared, M=M, K=K)
+    B.bwta_gemm_prepared(prepared, wsign, s_got, dev(s_w), None, out, fmt=fmt, M=M, N=N, K=K)
     torch.cuda.synchronize()
     assert torch.equal(_bits(s_got), _bits(dev(oracle.act_scale(base)))[idx])
     assert np.array_equal(oracle.act_scale(base).view(np.uint16), s_base.view(np.uint16))  # same scales as above
@@ -83,7 +83,7 @@ def test_more_than_2g_output_elements(entry):
     assert M * N > 2**31
     print("tall output", entry, M, N, K, flush=True)
     base = synth.gaussian_outlier_activations(22, 0, PERIOD, K)
-    s_base = synth.token_scales_l1(base)
+    s_base = oracle.act_scale(base)
     w = synth.binary_pm1(22, 1, (N, K))
     s_w = synth.scales(22, 2, N)
     _, acc_b, out_b = oracle.linear(base, s_base, w, s_w)

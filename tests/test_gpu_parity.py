@@ -12,7 +12,8 @@ import oracle
 from gpu_util import (dev, gpu_gemm, gpu_linear, gpu_pack_weights, gpu_quantize_pack, host_u32,
                       max_rel_err, same_half)
 from paper_2604_03957_amd import binding as B
-from paper_2604_03957_amd import synth
+import inputs
+import synth
 
 pytestmark = pytest.mark.gpu
 RTOL = 1e-3
@@ -119,8 +120,8 @@ def test_fragment_routes_every_half_pattern():
             _, want_acc, want_out = oracle.linear(A, s, w, ones)
             acc = torch.full((M, N), 123456, dtype=torch.int32, device="cuda:0")
             B.set_tile(0)
-            B.bwta_prepare_act(dev(A), dev(s), prep, M=M, K=K)
-            B.bwta_gemm_prepared(prep, wsign, dev(s), dev(ones), acc, None, M=M, N=N, K=K)
+            fmt = B.bwta_prepare_act(dev(A), dev(s), prep, M=M, K=K)
+            B.bwta_gemm_prepared(prep, wsign, dev(s), dev(ones), acc, None, fmt=fmt, M=M, N=N, K=K)
             torch.cuda.synchronize()
             assert np.array_equal(acc.cpu().numpy(), want_acc), rot
             out = torch.full((M, 128), 7.0, dtype=torch.float16, device="cuda:0")
@@ -330,7 +331,7 @@ def test_empty_problem_is_a_noop():
 @pytest.mark.parametrize("path", PATHS)
 @pytest.mark.parametrize("which", ["up", "down"])
 def test_linear_ffn_reduced_m(which, path):
-    c = synth.config2(which, M=200)
+    c = inputs.config2(which, M=200)
     _say("linear", c["name"], "path", path)
     _, _, want = oracle.linear(c["A"], c["s_a"], c["w"], c["s_w"])
     wsign = gpu_pack_weights(c["w"])
@@ -342,7 +343,7 @@ def test_linear_ffn_reduced_m(which, path):
 @pytest.mark.parametrize("path", PATHS)
 def test_linear_laplace_block_input(path):
     x = synth.laplace_activations(4, 1, 96, 4096)
-    s = synth.token_scales_l1(x)
+    s = oracle.act_scale(x)
     w = synth.binary_pm1(4, 10, (160, 4096))
     s_w = synth.scales(4, 11, 160)
     _, _, want = oracle.linear(x, s, w, s_w)
@@ -514,14 +515,14 @@ def test_prepare_once_feed_several_weight_matrices(path):
     prep = torch.empty(B.prepared_bytes(M, K), dtype=torch.uint8, device="cuda:0")
     B.set_path(path)
     try:
-        B.bwta_prepare_act(dev(A), dev(s), prep, M=M, K=K)
+        fmt = B.bwta_prepare_act(dev(A), dev(s), prep, M=M, K=K)
         for i, N in enumerate((40, 129)):
             w = synth.binary_pm1(60 + i, 1, (N, K))
             s_w = synth.scales(60 + i, 2, N)
             t, acc_want, want = oracle.linear(A, s, w, s_w)
             out = torch.empty((M, N), dtype=torch.float16, device="cuda:0")
             acc = torch.empty((M, N), dtype=torch.int32, device="cuda:0")
-            B.bwta_gemm_prepared(prep, gpu_pack_weights(w), dev(s), dev(s_w), acc, out, M=M, N=N, K=K)
+            B.bwta_gemm_prepared(prep, gpu_pack_weights(w), dev(s), dev(s_w), acc, out, fmt=fmt, M=M, N=N, K=K)
             torch.cuda.synchronize()
             assert np.array_equal(acc.cpu().numpy(), acc_want)
             assert same_half(out.cpu().numpy(), want)

@@ -9,7 +9,7 @@ import torch
 import oracle
 from gpu_util import dev, gpu_gemm, host_u32, max_rel_err, same_half
 from paper_2604_03957_amd import binding as B
-from paper_2604_03957_amd import synth
+import synth
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -114,8 +114,8 @@ def test_scale_and_ternarise_in_one_pass(M, N, K, lda, path):
         out = torch.full((M, N), 7.0, dtype=torch.float16, device=DEV)
         ws = torch.empty((N, B.plane_row_words(K)), dtype=torch.int32, device=DEV)
         B.bwta_pack_weights(dev(w), ws, N=N, K=K)
-        B.bwta_prepare_act_autoscale(dev(A), s, prep, M=M, K=K, lda=lda)
-        B.bwta_gemm_prepared(prep, ws, s, dev(s_w), None, out, M=M, N=N, K=K)
+        fmt = B.bwta_prepare_act_autoscale(dev(A), s, prep, M=M, K=K, lda=lda)
+        B.bwta_gemm_prepared(prep, ws, s, dev(s_w), None, out, fmt=fmt, M=M, N=N, K=K)
         torch.cuda.synchronize()
     finally:
         B.set_path(B.PATH_AUTO)

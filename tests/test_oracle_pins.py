@@ -11,7 +11,8 @@ import numpy as np
 import pytest
 
 import oracle
-from paper_2604_03957_amd import synth
+import inputs
+import synth
 
 ALL_HALF = np.arange(65536, dtype=np.uint32).astype(np.uint16)
 
@@ -286,7 +287,7 @@ def test_epilogue_against_exact_rational_product():
 
 
 def test_linear_is_the_composition():
-    c = synth.config2("up", M=8)
+    c = inputs.config2("up", M=8)
     t, acc, out = oracle.linear(c["A"], c["s_a"], c["w"], c["s_w"])
     assert np.array_equal(t, oracle.ternarize(c["A"], c["s_a"]))
     assert np.array_equal(acc, t.astype(np.int64) @ c["w"].astype(np.int64).T)
@@ -462,9 +463,14 @@ def test_prepare_weights_matches_float64_numpy_and_special_values():
 
 
 def test_act_scale_is_twice_the_mean_absolute_value():
-    c = synth.config2("up", M=16)
-    got = oracle.act_scale(c["A"])
-    assert np.array_equal(got.view(np.uint16), c["s_a"].view(np.uint16))      # the input recipe computes it in float64
+    A16 = synth.config2("up", M=16)["A"]
+    got = oracle.act_scale(A16)
+    ref = 2.0 * np.mean(np.abs(A16.astype(np.float64)), axis=1)               # float64: 1e-13 relative, then one rounding
+    assert np.all(np.abs(got.astype(np.float64) - ref) <= ref * 2.0 ** -11)
+    # random rows against exact rational arithmetic, rounded once to binary16 by bisection on the grid
+    rows = (synth.laplace(44, 1, 5 * 37) * np.repeat([1e-3, 0.3, 1.0, 40.0, 3000.0], 37)).astype(np.float16).reshape(5, 37)
+    want = [_half_of_fraction(2 * sum(abs(Fraction(float(x))) for x in r) / len(r)) for r in rows]
+    assert [x.view(np.uint16) for x in oracle.act_scale(rows)] == [x.view(np.uint16) for x in want]
     A = np.array([[1.0, -2.0, 0.5, 0.0], [6e-8, 6e-8, 0.0, 0.0], [65504.0] * 4], np.float16)
     with np.errstate(over="ignore"):
         want = [np.float16(1.75), _half_of_fraction(Fraction(float(np.float16(6e-8))) * 2 * 2 / 4), np.float16(np.inf)]
