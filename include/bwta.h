@@ -273,6 +273,9 @@ int bwta_set_path(int path);
 int bwta_get_path(void);
 /* Library version, major * 100 + minor. */
 int bwta_version(void);
+/* A short hex digest of the sources this library was built from (static storage): lets a
+ * measurement that was taken on one build be told apart from another build's. */
+const char *bwta_build_id(void);
 
 #ifdef __cplusplus
 }

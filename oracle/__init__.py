@@ -17,8 +17,13 @@ _LIB = os.path.join(_HERE, "libbwta_oracle.so")
 SCALE_NONE, SCALE_SCALAR, SCALE_VECTOR = 0, 1, 2
 
 
-def build(force=False):
-    """Compile the oracle with gcc (plain -O2, OpenMP for the row loops)."""
+def build(force=False, out=None, extra_flags=()):
+    """Compile the oracle with gcc (plain -O2, OpenMP for the row loops).  `out` / `extra_flags`:
+    a second build elsewhere, e.g. an instrumented one for the sanitizer test."""
+    if out is not None:
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra"]
+                              + list(extra_flags) + ["-o", out, _SRC, "-lm"])
+        return out
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + ".tmp%d" % os.getpid()
         subprocess.check_call(
@@ -34,7 +39,8 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        L = ctypes.CDLL(build())
+        # BWTA_ORACLE_LIB: load this build of the same source instead (the sanitizer test's)
+        L = ctypes.CDLL(os.environ.get("BWTA_ORACLE_LIB") or build())
         c = ctypes
         P = c.c_void_p
         L.bwta_oracle_num_threads.restype = c.c_int

@@ -12,7 +12,8 @@ import os
 import torch  # noqa: F401
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "csrc", "libbwta.so")
+# BWTA_LIB: load this build of the same sources instead (the sanitizer test's host-instrumented one)
+LIB_PATH = os.environ.get("BWTA_LIB") or os.path.join(_HERE, "csrc", "libbwta.so")
 
 OK = 0
 ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = -1, -2, -3, -4, -5, -6
@@ -24,7 +25,7 @@ KERNEL_GEMV_POPC, KERNEL_GEMV_FP4, KERNEL_GEMM_FP4, KERNEL_GEMM_MFMA_I8, KERNEL_
 
 EXPORTS = ["bwta_plane_row_words", "bwta_workspace_bytes", "bwta_quantize_pack_act",
            "bwta_pack_weights", "bwta_gemm", "bwta_linear", "bwta_strerror", "bwta_last_hip_error",
-           "bwta_set_path", "bwta_get_path", "bwta_auto_path", "bwta_linear_launches", "bwta_version", "bwta_set_tile",
+           "bwta_build_id", "bwta_set_path", "bwta_get_path", "bwta_auto_path", "bwta_linear_launches", "bwta_version", "bwta_set_tile",
            "bwta_prepared_bytes", "bwta_prepared_format", "bwta_planned_kernel", "bwta_prepare_act", "bwta_gemm_prepared", "bwta_gemm_grouped",
            "bwta_quantize_pack_bool", "bwta_matmul_tt", "bwta_prepare_weights", "bwta_act_scale",
            "bwta_prepare_act_autoscale", "bwta_matmul_bool_prepared"]
@@ -99,6 +100,7 @@ _lib.bwta_auto_path.argtypes = [_c.c_int, _c.c_int, _c.c_int]
 _lib.bwta_linear_launches.restype = _c.c_int
 _lib.bwta_linear_launches.argtypes = [_c.c_int, _c.c_int, _c.c_int]
 _lib.bwta_version.restype = _c.c_int
+_lib.bwta_build_id.restype = _c.c_char_p
 _lib.bwta_set_tile.restype = _c.c_int
 _lib.bwta_set_tile.argtypes = [_c.c_int]
 
@@ -188,6 +190,10 @@ def set_tile(tile):
 
 def version():
     return int(_lib.bwta_version())
+
+
+def build_id():
+    return _lib.bwta_build_id().decode()
 
 
 def bwta_quantize_pack_act(A, s_a, mask, sign, nnz=None, *, M, K, lda=None, a_dtype=DTYPE_FP16,

@@ -6,6 +6,7 @@ into objects under csrc/_build/ and then linked.  Every call compiles everything
 kept)."""
 import concurrent.futures
 import glob
+import hashlib
 import os
 import subprocess
 import sys
@@ -31,9 +32,19 @@ def _headers():
     return glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(HERE, "..", "include", "*.h"))
 
 
+def build_id():
+    """Digest of every source and header the library is built from (and of the compiler flags)."""
+    h = hashlib.sha1(" ".join(HIPCC_FLAGS).encode())
+    for f in sorted(sources() + _headers(), key=os.path.basename):
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:12]
+
+
 def build_library(verbose=True, extra_flags=(), incremental=False, jobs=8):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     os.makedirs(OBJ, exist_ok=True)
+    bid = build_id()
     newest_header = max(os.path.getmtime(h) for h in _headers())
     todo, objs = [], []
     for src in sources():
@@ -41,12 +52,14 @@ def build_library(verbose=True, extra_flags=(), incremental=False, jobs=8):
         objs.append(obj)
         fresh = (incremental and not extra_flags and os.path.exists(obj)
                  and os.path.getmtime(obj) > max(os.path.getmtime(src), newest_header))
-        if not fresh:
+        if not fresh or os.path.basename(src) == "bwta_api.hip":
             todo.append((src, obj))
 
     def compile_one(job):
         src, obj = job
         cmd = [hipcc] + HIPCC_FLAGS + list(extra_flags) + ["-c", src, "-o", obj]
+        if os.path.basename(src) == "bwta_api.hip":  # the one file that records the digest: always rebuilt
+            cmd.insert(-4, '-DBWTA_BUILD_ID="%s"' % bid)
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.check_call(cmd)

@@ -480,6 +480,11 @@ int bwta_planned_kernel(int operand, int M, int N, int K)
 
 int bwta_version(void) { return 2; }
 
+#ifndef BWTA_BUILD_ID
+#define BWTA_BUILD_ID "unknown"
+#endif
+const char *bwta_build_id(void) { return BWTA_BUILD_ID; }
+
 int bwta_set_tile(int tile)
 {
     if (tile >= 2000) {  // matrix-core decode kernel: 2000 + 1024 * ring depth + 64 * chunks-per-wavefront + tiles-per-workgroup

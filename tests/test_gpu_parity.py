@@ -560,6 +560,38 @@ def test_gemm_grouped_matches_oracle(M, N, K, count, path):
         assert same_half(out.cpu().numpy(), out_want)
 
 
+@pytest.mark.parametrize("path", [B.PATH_AUTO, B.PATH_POPC, B.PATH_FP4])
+@pytest.mark.parametrize("M", [1, 5, 12, 40])
+def test_gemm_grouped_mixed_null_scales(M, path):
+    """Problems of one grouped call may leave either scale out (NULL reads as 1) independently of
+    their neighbours, the first problem included."""
+    N, K = 150, 700
+    _say("grouped mixed scales", M, N, K, path)
+    t, _, s_a, _ = _gemm_case(3300 + M, M, N, K, p0=0.5)
+    mask, sign, _ = oracle.pack_act(t)
+    dm, dsg, dsa = dev(mask), dev(sign), dev(s_a)
+    have = [(False, False), (True, True), (False, True), (True, False), (True, True)]  # (s_a, s_w) present?
+    keep, probs, want = [], [], []
+    for i, (ha, hw) in enumerate(have):
+        w = synth.binary_pm1(3400 + i, M, (N, K))
+        s_w = synth.scales(3500 + i, M, N)
+        acc_want = oracle.gemm_unpacked(t, w)
+        want.append(oracle.epilogue(acc_want, s_a if ha else None, s_w if hw else None))
+        dw, dsw = gpu_pack_weights(w), dev(s_w)
+        out = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda:0")
+        keep.append((dw, dsw, out))
+        probs.append((dm, dsg, dw, dsa if ha else None, dsw if hw else None, None, out))
+    ws = torch.empty(max(B.workspace_bytes(M, N, K), 256) * len(have), dtype=torch.uint8, device="cuda:0")
+    B.set_path(path)
+    try:
+        B.bwta_gemm_grouped(B.make_problems(probs), ws, M=M, N=N, K=K)
+        torch.cuda.synchronize()
+    finally:
+        B.set_path(B.PATH_AUTO)
+    for i, ((dw, dsw, out), out_want) in enumerate(zip(keep, want)):
+        assert same_half(out.cpu().numpy(), out_want), (i, have[i])
+
+
 @pytest.mark.parametrize("path", [B.PATH_AUTO] + PATHS)
 @pytest.mark.parametrize("M,N,K", [(64, 96, 768), (3, 130, 1000), (130, 70, 129), (16, 257, 4096), (300, 200, 1000)])
 def test_binary_activations_w1a1(M, N, K, path):
