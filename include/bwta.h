@@ -51,7 +51,8 @@ enum {
     BWTA_ERR_ALIGN = -3,       /* a plane / output pointer or leading dimension is misaligned */
     BWTA_ERR_UNSUPPORTED = -4, /* unknown dtype, scale mode or path                        */
     BWTA_ERR_WORKSPACE = -5,   /* workspace NULL or smaller than bwta_workspace_bytes()    */
-    BWTA_ERR_HIP = -6          /* the HIP runtime reported an error at launch              */
+    BWTA_ERR_HIP = -6,         /* the HIP runtime reported an error at launch              */
+    BWTA_ERR_TOO_LARGE = -7    /* bwta_linear_static: the shape needs more than the static scratch */
 };
 
 enum { BWTA_DTYPE_FP16 = 0, BWTA_DTYPE_INT8 = 1 };
@@ -132,6 +133,30 @@ int bwta_linear(const void *A, int64_t lda, const void *s_a, int a_scale_mode,
                 const uint32_t *wsign, const void *s_w, int w_scale_mode, int M, int N, int K,
                 void *out, int64_t ldo, void *workspace, size_t workspace_bytes,
                 bwta_stream_t stream);
+
+/*
+ * bwta_linear for callers that cannot allocate or pass a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same
+ * bits as bwta_linear, except that the scratch is an array inside the library's own device image
+ * (BWTA_STATIC_SCRATCH_BYTES on every GPU the library is used on, held until the process ends)
+ * instead of a caller buffer.  The call allocates nothing and frees nothing.
+ *   - A shape with bwta_workspace_bytes(M, N, K) > BWTA_STATIC_SCRATCH_BYTES is refused with
+ *     BWTA_ERR_TOO_LARGE before anything is enqueued (32 MiB covers e.g. 2048 tokens at K = 11008
+ *     and 4096 tokens at K = 3072).
+ *   - All calls on one GPU share that GPU's array: calls that may overlap on the same GPU (two
+ *     streams, two threads) race; serialise them or use bwta_linear with separate workspaces.
+ *     Nothing in the array has to be cleared between calls.
+ *   - The array's address is looked up once per device (hipGetSymbolAddress, with that device
+ *     current) on the first call there; bwta_static_scratch_init() does the look-up for the current
+ *     device ahead of time, e.g. before a graph capture starts.  Both return BWTA_ERR_HIP if the
+ *     look-up fails.
+ */
+#define BWTA_STATIC_SCRATCH_BYTES (32u << 20)
+size_t bwta_static_scratch_bytes(void);
+int bwta_static_scratch_init(void);
+int bwta_linear_static(const void *A, int64_t lda, const void *s_a, int a_scale_mode,
+                       const uint32_t *wsign, const void *s_w, int w_scale_mode, int M, int N, int K,
+                       void *out, int64_t ldo, bwta_stream_t stream);
 
 /*
  * The two halves of bwta_linear as separate calls, so that one ternarisation can feed several

@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("BWTA_LIB") or os.path.join(_HERE, "csrc", "libbwta.so")
 
 OK = 0
-ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = -1, -2, -3, -4, -5, -6
+ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_TOO_LARGE = -1, -2, -3, -4, -5, -6, -7
 DTYPE_FP16, DTYPE_INT8 = 0, 1
 SCALE_NONE, SCALE_SCALAR, SCALE_VECTOR = 0, 1, 2
 PATH_AUTO, PATH_POPC, PATH_MFMA, PATH_FP4 = 0, 1, 2, 3
@@ -24,7 +24,8 @@ PREPARED_PLANES, PREPARED_FP4 = 1, 2
 KERNEL_GEMV_POPC, KERNEL_GEMV_FP4, KERNEL_GEMM_FP4, KERNEL_GEMM_MFMA_I8, KERNEL_GEMM_POPC = 1, 2, 3, 4, 5
 
 EXPORTS = ["bwta_plane_row_words", "bwta_workspace_bytes", "bwta_quantize_pack_act",
-           "bwta_pack_weights", "bwta_gemm", "bwta_linear", "bwta_strerror", "bwta_last_hip_error",
+           "bwta_pack_weights", "bwta_gemm", "bwta_linear", "bwta_linear_static", "bwta_static_scratch_bytes",
+           "bwta_static_scratch_init", "bwta_strerror", "bwta_last_hip_error",
            "bwta_build_id", "bwta_set_path", "bwta_get_path", "bwta_auto_path", "bwta_linear_launches", "bwta_version", "bwta_set_tile",
            "bwta_prepared_bytes", "bwta_prepared_format", "bwta_planned_kernel", "bwta_prepare_act", "bwta_gemm_prepared", "bwta_gemm_grouped",
            "bwta_quantize_pack_bool", "bwta_matmul_tt", "bwta_prepare_weights", "bwta_act_scale",
@@ -53,6 +54,11 @@ _lib.bwta_gemm.argtypes = [_P, _P, _P, _c.c_int, _c.c_int, _c.c_int, _P, _c.c_in
 _lib.bwta_linear.restype = _c.c_int
 _lib.bwta_linear.argtypes = [_P, _c.c_int64, _P, _c.c_int, _P, _P, _c.c_int, _c.c_int, _c.c_int,
                              _c.c_int, _P, _c.c_int64, _P, _c.c_size_t, _P]
+_lib.bwta_linear_static.restype = _c.c_int
+_lib.bwta_linear_static.argtypes = [_P, _c.c_int64, _P, _c.c_int, _P, _P, _c.c_int, _c.c_int, _c.c_int,
+                                    _c.c_int, _P, _c.c_int64, _P]
+_lib.bwta_static_scratch_bytes.restype = _c.c_size_t
+_lib.bwta_static_scratch_init.restype = _c.c_int
 _lib.bwta_prepared_bytes.restype = _c.c_size_t
 _lib.bwta_prepared_bytes.argtypes = [_c.c_int, _c.c_int]
 _lib.bwta_prepare_act.restype = _c.c_int
@@ -227,6 +233,22 @@ def bwta_linear(A, s_a, wsign, s_w, out, workspace, *, M, N, K, lda=None, ldo=No
     _check(_lib.bwta_linear(_ptr(A), lda, _ptr(s_a), _mode(s_a, a_scale_mode), _ptr(wsign), _ptr(s_w),
                             _mode(s_w, w_scale_mode), M, N, K, _ptr(out), ldo, _ptr(workspace),
                             workspace_bytes, _stream(stream)))
+
+
+def static_scratch_bytes():
+    return int(_lib.bwta_static_scratch_bytes())
+
+
+def static_scratch_init():
+    _check(_lib.bwta_static_scratch_init())
+
+
+def bwta_linear_static(A, s_a, wsign, s_w, out, *, M, N, K, lda=None, ldo=None, a_scale_mode=None,
+                       w_scale_mode=None, stream=None):
+    lda = K if lda is None else lda
+    ldo = N if ldo is None else ldo
+    _check(_lib.bwta_linear_static(_ptr(A), lda, _ptr(s_a), _mode(s_a, a_scale_mode), _ptr(wsign), _ptr(s_w),
+                                   _mode(s_w, w_scale_mode), M, N, K, _ptr(out), ldo, _stream(stream)))
 
 
 def bwta_quantize_pack_bool(A, s_a, mask, *, M, K, lda=None, scale_mode=None, stream=None):

@@ -4,10 +4,40 @@
 #include "../../include/bwta_tuning.h"
 
 #include <atomic>
+#include <mutex>
 
 #include "bwta_internal.h"
 
+// Scratch of the entry point that allocates nothing (bwta_linear_static): part of the library's
+// image on every GPU it runs on, until the process ends.  In host code this name is only a handle
+// for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[BWTA_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+// the array's address on each device, looked up once per device with that device current
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch_ptr(void **out, hipError_t *err)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess && (dev < 0 || dev >= kMaxDevices)) e = hipErrorInvalidDevice;
+    if (e == hipSuccess) {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[dev]) {
+            void *p = nullptr;
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e == hipSuccess && !p) e = hipErrorInvalidSymbol;
+            if (e == hipSuccess) g_scratch_ptr[dev] = p;
+        }
+        if (e == hipSuccess) *out = g_scratch_ptr[dev];
+    }
+    *err = e;
+    return e == hipSuccess ? BWTA_OK : BWTA_ERR_HIP;
+}
 
 std::atomic<int> g_path{BWTA_PATH_AUTO};
 thread_local int t_last_hip_error = 0;
@@ -191,6 +221,40 @@ int bwta_prepared_format(int M, int K)
 {
     if (M <= 0 || K <= 0) return BWTA_PREPARED_PLANES;
     return fp4_uses_fragments(M, K) ? BWTA_PREPARED_FP4 : BWTA_PREPARED_PLANES;
+}
+
+size_t bwta_static_scratch_bytes(void) { return BWTA_STATIC_SCRATCH_BYTES; }
+
+int bwta_static_scratch_init(void)
+{
+    void *p = nullptr;
+    hipError_t e;
+    int rc = static_scratch_ptr(&p, &e);
+    if (rc != BWTA_OK) t_last_hip_error = (int)e;
+    return rc;
+}
+
+int bwta_linear_static(const void *A, int64_t lda, const void *s_a, int a_scale_mode, const uint32_t *wsign,
+                       const void *s_w, int w_scale_mode, int M, int N, int K, void *out, int64_t ldo,
+                       bwta_stream_t stream)
+{
+    // the shape must fit before anything else is looked at: a caller sizing its batches to the limit
+    // gets this answer whatever else is wrong with the call
+    if (M > 0 && N > 0 && K > 0 && bwta_workspace_bytes(M, N, K) > BWTA_STATIC_SCRATCH_BYTES) return BWTA_ERR_TOO_LARGE;
+    void *ws = nullptr;
+    if (M > 0 && N > 0 && K > 0) {
+        hipError_t e;
+        int rc = static_scratch_ptr(&ws, &e);
+        if (rc != BWTA_OK) {
+            t_last_hip_error = (int)e;
+            return rc;
+        }
+    }
+    // Nothing in the scratch has to start from zero: the ternarisation kernels write every word the
+    // product kernels read (padding rows and k steps included), so the previous call's contents are
+    // simply overwritten.
+    return bwta_linear(A, lda, s_a, a_scale_mode, wsign, s_w, w_scale_mode, M, N, K, out, ldo, ws,
+                       ws ? (size_t)BWTA_STATIC_SCRATCH_BYTES : 0, stream);
 }
 
 size_t bwta_prepared_bytes(int M, int K)
@@ -431,6 +495,7 @@ const char *bwta_strerror(int code)
     case BWTA_ERR_UNSUPPORTED: return "unsupported dtype, scale mode or path";
     case BWTA_ERR_WORKSPACE: return "workspace missing or too small";
     case BWTA_ERR_HIP: return "HIP runtime error at launch (see bwta_last_hip_error)";
+    case BWTA_ERR_TOO_LARGE: return "the shape needs more scratch than the library's static scratch holds";
     default: return "unknown error code";
     }
 }

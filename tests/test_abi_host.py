@@ -227,3 +227,14 @@ def test_prepared_attention_product_rejects_bad_arguments():
     assert _code(f, FAKE, FAKE, None, None, FAKE, **dict(kw, ldo=64)) == B.ERR_SHAPE
     assert _code(f, FAKE, FAKE, None, None, FAKE, **dict(kw, strideA=8)) == B.ERR_SHAPE
     f(FAKE, FAKE, None, None, FAKE, **dict(kw, batch=0))
+
+
+def test_static_scratch_entry_point_refuses_oversized_shapes_on_the_host():
+    assert B.static_scratch_bytes() == 32 << 20
+    lin = B.bwta_linear_static
+    kw = dict(stream=0, a_scale_mode=B.SCALE_VECTOR, w_scale_mode=B.SCALE_VECTOR)
+    assert B.workspace_bytes(8192, 768, 11008) > B.static_scratch_bytes()
+    assert _code(lin, FAKE, FAKE, FAKE, FAKE, FAKE, M=8192, N=768, K=11008, **kw) == B.ERR_TOO_LARGE
+    assert _code(lin, None, None, None, None, None, M=8192, N=768, K=11008, **kw) == B.ERR_TOO_LARGE  # size first
+    assert B.strerror(B.ERR_TOO_LARGE) != "unknown error code"
+    lin(FAKE, FAKE, FAKE, FAKE, FAKE, M=0, N=768, K=11008, **kw)   # empty: a no-op, no device needed
