@@ -32,7 +32,9 @@ int bwta_planned_kernel(int operand, int M, int N, int K);
 int bwta_linear_launches(int M, int N, int K);
 /* Tuning hook for benchmark sweeps: force the FP4 kernel's per-wavefront tile (22, 21, 12, 11, 13
  * = blocks of 32 rows x 32 columns per wavefront; 23 = 22 at three wavefronts per SIMD; 222 = 22
- * with K split over two groups of wavefronts), the popcount decode kernel's row split (1000 + 16 *
+ * with K split over two groups of wavefronts; 243, 223, 323 = the kernel that stages both operands
+ * through LDS with direct loads, as 128 x 256 tiles of 8 wavefronts, 128 x 128 tiles of 4, or
+ * 128 x 256 tiles of 4 wavefronts of 64 tokens x 128 channels), the popcount decode kernel's row split (1000 + 16 *
  * lanes per row (8, 16, 32) + chunks per lane; ignored where the registers cannot hold it) or the
  * matrix-core decode kernel's work split (2000 + 1024 * ring depth (2..4) + 64 * chunks per
  * wavefront (1..4) + tiles per workgroup (rounded up to a multiple of the ring depth, fewer if LDS

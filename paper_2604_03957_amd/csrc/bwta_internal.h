@@ -66,6 +66,8 @@ hipError_t launch_att_v_fp4(const GemmArgs &g, const uint32_t *frag, int batch, 
                             int64_t out_stride, float alpha, hipStream_t st);
 void set_gemv_tile(int g, int nch);
 hipError_t launch_gemm_fp4(const GemmArgs &g, uint32_t *frag, bool frag_ready, hipStream_t st);
+bool gemm_fp4_lds_supported(const GemmArgs &g);
+hipError_t launch_gemm_fp4_lds(const GemmArgs &g, const uint32_t *frag, int variant, hipStream_t st);
 hipError_t launch_quantize_to_fp4(const void *A, int64_t lda, ScaleArg s_a, int M, int K, uint32_t *frag,
                                   hipStream_t st);
 hipError_t launch_act_scale_quantize(const void *A, int64_t lda, int M, int K, uint16_t *s_out, uint32_t *frag,

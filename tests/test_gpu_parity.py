@@ -608,3 +608,40 @@ def test_binary_activations_w1a1(M, N, K, path):
     acc, out = gpu_gemm(None, xs, wsn, s_a, s_w, M, N, K, path=path)
     assert np.array_equal(acc, want_acc)
     assert same_half(out, oracle.epilogue(want_acc, s_a, s_w))
+
+
+@pytest.mark.parametrize("variant", [223, 243, 323])
+@pytest.mark.parametrize("M,N,K", [(129, 256, 256), (300, 200, 1000), (257, 513, 2100), (1000, 700, 4096), (130, 90, 11008),
+                                   (1000, 704, 4096), (256, 288, 256), (136, 64, 11008), (2048, 1024, 768),
+                                   (4096, 4608, 384)])
+def test_lds_staged_tiled_kernel_variants(M, N, K, variant):
+    """The tiled FP4 kernel whose operands reach LDS by direct global->LDS loads, every tile / ring
+    variant forced through the tuning hook: int32 accumulators and fp16 outputs, from planes
+    (bwta_gemm) and from fp16 activations (bwta_linear's two-kernel form)."""
+    _say("lds-staged", M, N, K, variant)
+    t, w, s_a, s_w = _gemm_case(5000 + M + variant, M, N, K, p0=0.5)
+    mask, sign, _ = oracle.pack_act(t)
+    wsign = oracle.pack_weights(w)
+    want_acc = oracle.gemm_unpacked(t, w)
+    want_out = oracle.epilogue(want_acc, s_a, s_w)
+    B.set_tile(variant)
+    try:
+        acc, out = gpu_gemm(mask, sign, wsign, s_a, s_w, M, N, K, path=B.PATH_FP4, want_acc=True, want_out=False)
+        assert np.array_equal(acc, want_acc)
+        _, out = gpu_gemm(mask, sign, wsign, s_a, s_w, M, N, K, path=B.PATH_FP4, want_acc=False, want_out=True)
+        assert same_half(out, want_out)
+        # from fp16 activations: +-1 / 0 under a unit scale ternarise to themselves
+        B.set_tile(variant)
+        A16 = t.astype(np.float16)
+        dA = dev(A16)
+        prep = torch.empty(B.prepared_bytes(M, K), dtype=torch.uint8, device="cuda:0")
+        B.set_path(B.PATH_FP4)
+        if B.prepared_format(M, K) == B.PREPARED_FP4:
+            fmt = B.bwta_prepare_act(dA, None, prep, M=M, K=K)
+            o2 = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda:0")
+            B.bwta_gemm_prepared(prep, dev(wsign), dev(s_a), dev(s_w), None, o2, fmt=fmt, M=M, N=N, K=K)
+            torch.cuda.synchronize()
+            assert same_half(o2.cpu().numpy(), want_out)
+    finally:
+        B.set_path(B.PATH_AUTO)
+        B.set_tile(0)
