@@ -705,8 +705,51 @@ class Block:
     def _lin(self, prep, s_a, nm, out, K, N):
         self.B.bwta_gemm_prepared(prep, self.w[nm], s_a, self.sw[nm], None, out, fmt=self.fmt, M=self.S, N=N, K=K)
 
-    def forward(self, bwta_only=False):
-        """bwta_only: run just the 4 ternarisations and 7 products on whatever the buffers hold."""
+    def _attention_buffers(self):
+        torch, B, S, heads, hd = self.torch, self.B, self.S, self.heads, self.H // self.heads
+        if hasattr(self, "scores"):
+            return
+        dev = "cuda:0"
+        rw_d, rw_s = B.plane_row_words(hd), B.plane_row_words(S)
+        i32 = lambda *shape: torch.empty(shape, dtype=torch.int32, device=dev)
+        f16 = lambda *shape: torch.empty(shape, dtype=torch.float16, device=dev)
+        self.qm, self.qs, self.km, self.ks = (i32(heads * S, rw_d) for _ in range(4))
+        self.am = i32(heads * S, rw_s)
+        self.s_q, self.s_k, self.s_p = f16(heads * S), f16(heads * S), f16(heads * S)
+        self.s_v = f16(heads * hd)
+        self.prep_v = torch.empty(B.prepared_bytes(heads * hd, S), dtype=torch.uint8, device=dev)
+        self.scores = f16(heads, S, S)
+        self.ctx = f16(heads, S, hd)
+        self.causal = torch.ones((S, S), dtype=torch.bool, device=dev).triu_(1)
+
+    def bwta_attention(self):
+        """The paper's attention MatMuls in place of fp16 attention: scores = BWTA_QK(ternary(Q),
+        ternary(K)) / sqrt(d) (arithmetic Case 3), context = BWTA_Att(bool(softmax), ternary(V))
+        (Case 2).  Every operand's scale is the value training starts it from, per row (2 mean|.|),
+        computed by the library; the causal mask, the softmax and the head-major / transposed
+        layouts are plain tensor ops of the caller."""
+        torch, B, S, heads, hd = self.torch, self.B, self.S, self.heads, self.H // self.heads
+        self._attention_buffers()
+        rows = heads * S
+        self.qh = self.q.view(S, heads, hd).transpose(0, 1).contiguous().view(rows, hd)
+        self.kh = self.k.view(S, heads, hd).transpose(0, 1).contiguous().view(rows, hd)
+        self.vt = self.v.view(S, heads, hd).permute(1, 2, 0).contiguous().view(heads * hd, S)
+        for x, s, m, sg in ((self.qh, self.s_q, self.qm, self.qs), (self.kh, self.s_k, self.km, self.ks)):
+            B.bwta_act_scale(x, s, M=rows, K=hd)
+            B.bwta_quantize_pack_act(x, s, m, sg, None, M=rows, K=hd)
+        B.bwta_matmul_tt(self.qm, self.qs, self.km, self.ks, self.s_q, self.s_k, None, self.scores, batch=heads, M=S, N=S,
+                         K=hd, alpha=1.0 / hd ** 0.5)
+        self.probs = torch.softmax(self.scores.masked_fill(self.causal, float("-inf")), dim=-1, dtype=torch.float32).half()
+        pr = self.probs.view(rows, S)
+        B.bwta_act_scale(pr, self.s_p, M=rows, K=S)
+        B.bwta_quantize_pack_bool(pr, self.s_p, self.am, M=rows, K=S)
+        fmt = B.bwta_prepare_act_autoscale(self.vt, self.s_v, self.prep_v, M=heads * hd, K=S)
+        B.bwta_matmul_bool_prepared(self.am, self.prep_v, self.s_p, self.s_v, self.ctx, fmt=fmt, batch=heads, M=S, N=hd, K=S)
+        return self.ctx.transpose(0, 1).reshape(S, self.H).contiguous()
+
+    def forward(self, bwta_only=False, attention="fp16"):
+        """bwta_only: run just the 4 ternarisations and 7 products on whatever the buffers hold.
+        attention: "fp16" (plain reference attention) or "bwta" (the paper's two attention MatMuls)."""
         torch, B, S, H, F = self.torch, self.B, self.S, self.H, self.F
         h = self.h if bwta_only else self._norm(self.x)
         s = self.s_h = self._prep(h, self.prep_h, H)
@@ -714,6 +757,8 @@ class Block:
             self._lin(self.prep_h, s, nm, out, H, H)
         if bwta_only:
             att = self.att
+        elif attention == "bwta":
+            att = self.bwta_attention()
         else:
             hd = H // self.heads
             q, k, v = (t.view(S, self.heads, hd).transpose(0, 1).unsqueeze(0) for t in (self.q, self.k, self.v))
@@ -746,6 +791,11 @@ def run_c5(args, torch, B, synth):
     steps = max(5, args.steps // 10)
     ms_block = _event_ms(torch, blk.forward, steps, 3)
     ms_bwta = _event_ms(torch, lambda: blk.forward(bwta_only=True), steps, 3)
+    y2 = blk.forward(attention="bwta")
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(y2).all()), "block output is not finite (BWTA attention)"
+    ms_block_att = _event_ms(torch, lambda: blk.forward(attention="bwta"), steps, 3)
+    ms_att = _event_ms(torch, blk.bwta_attention, steps, 3)
     S, H, F = blk.S, blk.H, blk.F
     ops = 2.0 * S * (4 * H * H + 3 * H * F)
     return {"metric": "BWTA decoder block latency (7 BWTA linears + fp16 attention/norms)", "value": round(ms_block * 1e3, 1),
@@ -755,8 +805,13 @@ def run_c5(args, torch, B, synth):
             "config": {"workload": "c5_block: hidden 4096, FFN 11008, 32 heads, seq 2048, batch 1; Laplace(0,1) input"},
             "kernels": {"bwta_part_us": round(ms_bwta * 1e3, 1), "bwta_share": round(ms_bwta / ms_block, 3),
                         "bwta_effective_TOPS": round(ops / (ms_bwta * 1e-3) / 1e12, 1),
+                        "block_with_bwta_attention_us": round(ms_block_att * 1e3, 1),
+                        "bwta_attention_part_us": round(ms_att * 1e3, 1),
                         "note": "bwta part = 4 ternarisations (each computing its per-token scales in the same "
-                                "pass) + 7 products; the rest is torch fp16 attention, RMSNorm, SiLU and residuals"}}
+                                "pass) + 7 products; the rest is torch fp16 attention, RMSNorm, SiLU and residuals.  "
+                                "block_with_bwta_attention: the same block with the paper's attention MatMuls "
+                                "(BWTA_QK ternary x ternary, BWTA_Att bool x ternary; its part = head-major copies, "
+                                "scales, packers, both products, causal softmax) in place of fp16 attention"}}
 
 
 def run_prep(args, torch, B, synth):

@@ -185,3 +185,54 @@ def test_config5_block_ragged_sequence():
     torch.cuda.synchronize()
     assert y.shape == (333, 4096) and bool(torch.isfinite(y).all())
     _check_block_linears(blk, cfg)
+
+
+def _check_block_attention(blk):
+    """The block's two attention MatMuls against the oracle on the block's own tensors, every head and
+    every element: the per-row scales (the s_A^0 statistic), BWTA_QK = ternary(Q) (x) ternary(K)^T with
+    the 1/sqrt(d) prefix (arithmetic Case 3), and BWTA_Att = bool(softmax) (x) ternary(V) (Case 2)."""
+    host = lambda t: t.detach().cpu().numpy()
+    S, heads, hd = blk.S, blk.heads, blk.H // blk.heads
+    qh, kh, vt = host(blk.qh), host(blk.kh), host(blk.vt)
+    s_q, s_k, s_v = oracle.act_scale(qh), oracle.act_scale(kh), oracle.act_scale(vt)
+    for got, want, name in ((blk.s_q, s_q, "s_q"), (blk.s_k, s_k, "s_k"), (blk.s_v, s_v, "s_v")):
+        assert np.array_equal(host(got).view(np.uint16), want.view(np.uint16)), name
+    tq, tk, tv = oracle.ternarize(qh, s_q), oracle.ternarize(kh, s_k), oracle.ternarize(vt, s_v)
+    alpha = 1.0 / hd ** 0.5
+    scores = host(blk.scores)
+    for h in range(heads):
+        r = slice(h * S, (h + 1) * S)
+        want = oracle.epilogue_alpha(oracle.gemm_unpacked(tq[r], tk[r]), s_q[r], s_k[r], alpha)
+        assert not np.isnan(want).any() and same_half(scores[h], want), ("scores", h)
+    print("block attention scores ok", scores.shape, flush=True)
+    del scores
+    probs = host(blk.probs).reshape(heads * S, S)
+    assert np.isfinite(probs).all()
+    s_p = oracle.act_scale(probs)
+    assert np.array_equal(host(blk.s_p).view(np.uint16), s_p.view(np.uint16))
+    ctx = host(blk.ctx)
+    ones = 0
+    for h in range(heads):
+        r = slice(h * S, (h + 1) * S)
+        b = oracle.boolize(probs[r], s_p[r])
+        ones += int(b.sum())
+        d = slice(h * hd, (h + 1) * hd)
+        want = oracle.epilogue_alpha(oracle.gemm_unpacked(b, tv[d]), s_p[r], s_v[d], 1.0)
+        assert not np.isnan(want).any() and same_half(ctx[h], want), ("context", h)
+    assert 0 < ones < heads * S * S // 2                       # the boolean attention is neither empty nor dense
+    print("block attention context ok", ctx.shape, "ones per row %.1f" % (ones / (heads * S)), flush=True)
+
+
+@pytest.mark.parametrize("seq", [2048, 333])
+def test_config5_block_with_bwta_attention(seq):
+    """The block with the paper's attention MatMuls instead of fp16 attention: both attention products
+    and all 7 linears (whose inputs now come out of that attention) against the oracle, full size and a
+    ragged sequence."""
+    import bench
+    cfg = synth.config5(seq=seq)
+    blk = bench.Block(cfg, torch, B)
+    y = blk.forward(attention="bwta")
+    torch.cuda.synchronize()
+    assert y.shape == (seq, 4096) and bool(torch.isfinite(y).all())
+    _check_block_attention(blk)
+    _check_block_linears(blk, cfg)
