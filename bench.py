@@ -853,8 +853,7 @@ def run_short_k(args, torch, B, synth):
     for (M, N, K) in [(4096, 768, 768), (4096, 768, 256), (4096, 3072, 256), (1024, 768, 768), (4096, 3072, 768),
                       (128, 768, 768), (16, 3072, 768)]:
         A = np.ascontiguousarray(np.tile(base["A"], (1, 2))[:M, :K])
-        c = dict(M=M, N=N, K=K, A=A, s_a=base["s_a"][:M], w=synth.binary_pm1(8, N + K, (N, K)), s_w=synth.scales(8, 4, N),
-                 name="short_k")
+        c = dict(M=M, N=N, K=K, A=A, w=synth.binary_pm1(8, N + K, (N, K)), s_w=synth.scales(8, 4, N), name="short_k")
         L = Layer(c, torch, B, from_fp16=True)
         B.set_tile(900)
         two = _event_ms(torch, lambda: L.linear(B), args.steps, args.warmup)
