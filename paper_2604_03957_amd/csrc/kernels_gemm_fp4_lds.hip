@@ -43,6 +43,16 @@ typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int WM = 2;  // token blocks of 32 per wavefront
 
+// f(integral_constant<T>), ..., f(integral_constant<N - 1>): a loop whose counter is a compile-time constant
+template <int T, int N, class F>
+__device__ __forceinline__ void static_for(const F &f)
+{
+    if constexpr (T < N) {
+        f(std::integral_constant<int, T>{});
+        static_for<T + 1, N>(f);
+    }
+}
+
 template <int WN, int WAVES_M, int WAVES_N, int S>
 struct LCfg {
     static constexpr int BM = 32 * WM * WAVES_M, BN = 32 * WN * WAVES_N;
@@ -53,9 +63,13 @@ struct LCfg {
     static constexpr int A_ROUNDS = AF / NW, W_ROUNDS = WB / NW;  // direct loads per wavefront and slab
     static constexpr int LOADS = A_ROUNDS + W_ROUNDS;
     static constexpr int STRIP_HALFS = 32 * (32 * WN + 8);
-    static constexpr int EPI_BYTES = (BN + BM) * 4 + NW * STRIP_HALFS * 2;
-    static constexpr int RING_BYTES = S * STAGE_BYTES;
-    static constexpr int SMEM_BYTES = RING_BYTES > EPI_BYTES ? RING_BYTES : EPI_BYTES;
+    // epilogue scratch lives in the S - 1 stages the last slab does not use: scales and the first strips
+    // in the first of them, the other strips in the following ones
+    static constexpr int SCALE_BYTES = ((BN + BM) * 4 + 255) / 256 * 256;
+    static constexpr int EPI_FIRST = (STAGE_BYTES - SCALE_BYTES) / (STRIP_HALFS * 2);
+    static constexpr int EPI_PER_STAGE = STAGE_BYTES / (STRIP_HALFS * 2);
+    static constexpr int SMEM_BYTES = S * STAGE_BYTES;
+    static_assert(S >= 2 && EPI_FIRST + (S - 2) * EPI_PER_STAGE >= NW, "the free stages hold every wavefront's strip");
     static_assert(AF % NW == 0 && WB % NW == 0, "every wavefront issues the same loads per slab");
     static_assert(BN <= THREADS && BM <= THREADS, "one thread per scale");
     static_assert(SMEM_BYTES <= 160 * 1024, "LDS of one compute unit");
@@ -261,29 +275,59 @@ void k_gemm_fp4_lds(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, in
     const uint32_t a_rd = lds0 + (uint32_t)((wm * WM) * 4096 + lane * 16);                          // + i 4096 + step 1024
     const uint32_t w_rd = lds0 + (uint32_t)(C::A_BYTES + (wn * WN) * 1024 + r32 * 16 + h * 8);      // + j 1024 (+ 512: steps 2, 3)
 
+    // One slab: wait for the own requests of it (YOUNGER slabs of this wavefront may stay in flight: loads
+    // complete in order and every wavefront issues LOADS per slab), then the barrier after which everyone's
+    // have landed and everyone is done reading the previous slab.
     int stage = 0;
-    for (int it = 0; it < nslab; ++it) {
-        // own requests of this slab have landed (the S - 2 younger slabs may still be in flight) ...
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * C::LOADS) : "memory");
-        __builtin_amdgcn_s_barrier();  // ... and everyone else's; everyone is done reading the previous slab
-        {
-            const int nxt = it + S - 1;
-            int st_n = stage + S - 1;
-            st_n = st_n >= S ? st_n - S : st_n;
-            request(nxt < nslab ? nxt : nslab - 1, st_n);  // the tail re-requests the last slab: constant counts
-        }
+    auto slab = [&](auto younger, auto before_barrier, auto after_barrier) {
+        __builtin_amdgcn_sched_barrier(0);  // the previous slab's MFMAs stay in front of the wait
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(decltype(younger)::value * C::LOADS) : "memory");
+        before_barrier();
+        __builtin_amdgcn_s_barrier();
+        after_barrier();
         const uint32_t a_addr = a_rd + (uint32_t)(stage * C::STAGE_BYTES), w_addr = w_rd + (uint32_t)(stage * C::STAGE_BYTES);
         stage = stage + 1 == S ? 0 : stage + 1;
         slab_compute<WN>(acc, a_addr, w_addr, m88, c22);
+    };
+    auto nothing = [] {};
+    // slabs that still have a successor S - 1 ahead: request it into the stage the previous slab was read from
+    for (int it = 0; it + S - 1 < nslab; ++it)
+        slab(std::integral_constant<int, S - 2>{}, nothing, [&] {
+            int st_n = stage + S - 1;
+            st_n = st_n >= S ? st_n - S : st_n;
+            request(it + S - 1, st_n);
+        });
+    // The last S - 1 slabs request nothing: ever fewer loads stay in flight, and the stages they would
+    // have filled are free.  The stage behind the last slab's takes the scales (written before the last
+    // barrier, which publishes them); it and the one after it take the wavefronts' epilogue strips.  So a
+    // wavefront goes from its last MFMA into its epilogue without waiting for anyone.
+    float *sc_lds = nullptr;  // [BN] channel scales, then [BM] token scales
+    static_for<0, S - 1>([&](auto t) {
+        constexpr int T = decltype(t)::value;  // the slab nslab - (S - 1) + T; S - 2 - T younger ones in flight
+        if constexpr (T < S - 2)
+            slab(std::integral_constant<int, S - 2 - T>{}, nothing, nothing);
+        else
+            slab(std::integral_constant<int, 0>{},
+                 [&] {
+                     const int st_f = stage + 1 == S ? 0 : stage + 1;
+                     sc_lds = (float *)(smem + st_f * (C::STAGE_BYTES / 4));
+                     if (tid < C::BN) sc_lds[tid] = have_sw ? half_bits_to_float(sw_bits) : (want_sw ? 1.0f : 0.0f);
+                     if (tid < C::BM) sc_lds[C::BN + tid] = have_sa ? half_bits_to_float(sa_bits) : (want_sa ? 1.0f : 0.0f);
+                 },
+                 nothing);
+    });
+    // `stage` now names the stage behind the last slab's; wavefronts 0 .. EPI_FIRST - 1 put their strips
+    // behind the scales, the others into the stages that follow
+    int st_e = stage;
+    int slot = wave;
+    uint32_t strip_off = C::SCALE_BYTES;
+    if (wave >= C::EPI_FIRST) {
+        slot = wave - C::EPI_FIRST;
+        st_e = stage + 1 + slot / C::EPI_PER_STAGE;
+        st_e = st_e >= S ? st_e - S : st_e;
+        slot = slot % C::EPI_PER_STAGE;
+        strip_off = 0;
     }
-
-    // ---- every direct load has landed and every wavefront is done reading: the ring becomes scratch
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    float *sc_lds = (float *)smem;  // [BN] channel scales, then [BM] token scales
-    if (tid < C::BN) sc_lds[tid] = have_sw ? half_bits_to_float(sw_bits) : (want_sw ? 1.0f : 0.0f);
-    if (tid < C::BM) sc_lds[C::BN + tid] = have_sa ? half_bits_to_float(sa_bits) : (want_sa ? 1.0f : 0.0f);
-    __syncthreads();
 
     const int m_wave = m0 + wm * WM * 32, n_wave = n0 + wn * WN * 32;
     if (WITH_ACC && g.acc) {
@@ -300,7 +344,7 @@ void k_gemm_fp4_lds(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, in
         }
     }
     if (!g.out) return;
-    uint16_t *strip = (uint16_t *)(smem + C::BN + C::BM) + wave * C::STRIP_HALFS;
+    uint16_t *strip = (uint16_t *)((char *)smem + st_e * C::STAGE_BYTES + strip_off) + slot * C::STRIP_HALFS;
     store_tile_fp16<WM, WN>(acc, g, sc_lds + C::BN + wm * WM * 32, sc_lds + wn * WN * 32, strip, m_wave, n_wave, lane);
 }
 
@@ -318,6 +362,7 @@ hipError_t launch_lds(const GemmArgs &g, const uint32_t *frag, int s_pad, hipStr
         if (e != hipSuccess) return e;
         configured = true;
     }
+    if ((s_pad >> 2) < S - 1) return hipErrorInvalidValue;  // the kernel's tail runs S - 1 slabs (the padding gives 2)
     const int tiles_n = (g.N + C::BN - 1) / C::BN, tiles_m = (g.M + C::BM - 1) / C::BM;
     const int64_t total = (int64_t)tiles_n * tiles_m;
     if (total > 0x7fffffff) return hipErrorInvalidValue;
