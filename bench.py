@@ -414,12 +414,12 @@ def run_headline(args, torch, B, synth):
     dom_us = kern[dom]["k_gemm_fp4_alone_us"]
     achieved = L.ops / (dom_us * 1e-6) / 1e12
     roofline = {"bound": "mfma",
-                "kernel": "k_gemm_fp4 (tiled FP4 MFMA product + scale epilogue) on %s, M=%d N=%d K=%d, %.2f us per launch"
+                "kernel": "k_gemm_fp4_lds (LDS-staged tiled FP4 MFMA product + scale epilogue) on %s, M=%d N=%d K=%d, %.2f us per launch"
                           % (kern[dom]["layer"], L.M, L.N, L.K, dom_us),
                 "achieved": round(achieved, 1), "peak": PEAK_FP4_TOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_FP4_TOPS, 4), "frac_of_int8_peak": round(achieved / PEAK_INT8_TOPS, 4),
                 "flops_per_launch": L.ops,
-                "traffic": _traffic_from_profiles(B, "k_gemm_fp4", "M=%d N=%d K=%d" % (L.M, L.N, L.K)),
+                "traffic": _traffic_from_profiles(B, "k_gemm_fp4_lds", "M=%d N=%d K=%d" % (L.M, L.N, L.K)),
                 "whole_step_frac_of_int8_peak": round(value / PEAK_INT8_TOPS, 4),
                 "whole_step_frac_of_fp4_peak": round(value / PEAK_FP4_TOPS, 4)}
     out = {"metric": "BWTA GEMM effective TOPS (prefill) + achieved HBM GB/s (decode), 1 MI355X",
