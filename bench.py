@@ -420,6 +420,9 @@ def run_headline(args, torch, B, synth):
                 "frac": round(achieved / PEAK_FP4_TOPS, 4), "frac_of_int8_peak": round(achieved / PEAK_INT8_TOPS, 4),
                 "flops_per_launch": L.ops,
                 "traffic": _traffic_from_profiles(B, "k_gemm_fp4_lds", "M=%d N=%d K=%d" % (L.M, L.N, L.K)),
+                # the same three products on operands already in the kernel's fragment layout (what
+                # bwta_linear / bwta_prepare_act feed it): sum of the per-shape kernel times above
+                "step_from_prepared_operands_TOPS": round(sum(L_.ops for L_ in layers) / sum(k["k_gemm_fp4_alone_us"] for k in kern) / 1e6, 1),
                 "whole_step_frac_of_int8_peak": round(value / PEAK_INT8_TOPS, 4),
                 "whole_step_frac_of_fp4_peak": round(value / PEAK_FP4_TOPS, 4)}
     out = {"metric": "BWTA GEMM effective TOPS (prefill) + achieved HBM GB/s (decode), 1 MI355X",
