@@ -138,3 +138,35 @@ def test_attention_products_twice(path):
         _twice(run)
     finally:
         B.set_path(B.PATH_AUTO)
+
+
+@pytest.mark.parametrize("variant", [243, 223, 323])
+@pytest.mark.parametrize("M,N,K", [(700, 900, 3000), (2048, 4096, 4096), (130, 520, 512)])
+def test_lds_staged_kernel_twice(M, N, K, variant):
+    """The LDS-staged tiled kernel, whose wavefronts enter the epilogue without a workgroup barrier:
+    int32 accumulators and fp16 outputs of two runs must be the same bits."""
+    print("determinism lds-staged", M, N, K, variant, flush=True)
+    t = dev(synth.ternary(73, 1, (M, K), 0.5))
+    s_a = dev(synth.scales(73, 2, M))
+    s_w = dev(synth.scales(73, 3, N))
+    wsign = gpu_pack_weights(synth.binary_pm1(73, 4, (N, K)))
+    rw = B.plane_row_words(K)
+    mask = torch.empty((M, rw), dtype=torch.int32, device=DEV)
+    sign = torch.empty_like(mask)
+    B.bwta_quantize_pack_act(t, None, mask, sign, None, M=M, K=K, a_dtype=B.DTYPE_INT8)
+
+    def run():
+        ws = torch.zeros(B.workspace_bytes(M, N, K), dtype=torch.uint8, device=DEV)
+        acc = torch.full((M, N), -9, dtype=torch.int32, device=DEV)
+        out = torch.full((M, N), float("nan"), dtype=torch.float16, device=DEV)
+        B.bwta_gemm(mask, sign, wsign, s_a, s_w, acc, None, ws, M=M, N=N, K=K)
+        B.bwta_gemm(mask, sign, wsign, s_a, s_w, None, out, ws, M=M, N=N, K=K)
+        return [acc, out]
+
+    B.set_path(B.PATH_FP4)
+    B.set_tile(variant)
+    try:
+        _twice(run)
+    finally:
+        B.set_tile(0)
+        B.set_path(B.PATH_AUTO)
