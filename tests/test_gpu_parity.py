@@ -645,3 +645,37 @@ def test_lds_staged_tiled_kernel_variants(M, N, K, variant):
     finally:
         B.set_path(B.PATH_AUTO)
         B.set_tile(0)
+
+
+def test_lds_staged_seeded_random_shapes():
+    """30 seeded random problems on the LDS-staged tiled kernel (every tile variant in turn, forced
+    through the tuning hook): ragged token and channel counts, any K from two slabs up, planted
+    ties / infinities / NaN, from fp16 through bwta_linear's two-kernel form and from planes,
+    int32 and fp16."""
+    rng = np.random.default_rng(20261128)
+    variants = [243, 223, 323]
+    for case in range(30):
+        M, N, K = int(rng.integers(129, 900)), int(rng.integers(1, 1300)), int(rng.integers(129, 7000))  # tiled-kernel token counts
+        variant = variants[case % 3]
+        _say("random lds-staged problem", case, M, N, K, variant)
+        A = (synth.gaussian(9500 + case, 1, M * K) * float(rng.uniform(0.01, 30))).astype(np.float16).reshape(M, K)
+        s = oracle.act_scale(A)
+        flat = A.reshape(-1)
+        idx = rng.integers(0, flat.size, 6)
+        flat[idx[0]] = np.float16(0.5) * s[idx[0] // K]
+        flat[idx[1]] = -(np.float16(0.5) * s[idx[1] // K])
+        flat[idx[2]], flat[idx[3]], flat[idx[4]], flat[idx[5]] = np.inf, -np.inf, np.nan, -0.0
+        w = synth.binary_pm1(9600 + case, 2, (N, K))
+        s_w = synth.scales(9700 + case, 3, N)
+        t, acc_want, want = oracle.linear(A, s, w, s_w)
+        wsign = gpu_pack_weights(w)
+        mask, sign, _ = oracle.pack_act(t)
+        B.set_tile(variant)
+        try:
+            acc, out = gpu_gemm(mask, sign, wsign, s, s_w, M, N, K, path=B.PATH_FP4)
+            assert np.array_equal(acc, acc_want) and same_half(out, want), (case, M, N, K, variant)
+            B.set_tile(variant)
+            if K > 1024:  # longer than the one-launch linear takes: ternarise to fragments, then this kernel
+                assert same_half(gpu_linear(A, s, wsign, s_w, N, path=B.PATH_FP4), want), (case, M, N, K, variant)
+        finally:
+            B.set_tile(0)
