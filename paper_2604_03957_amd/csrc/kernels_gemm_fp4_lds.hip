@@ -21,14 +21,17 @@
 //     lane (r, h) of the MFMA finds the words of its four steps with two 8-byte reads.
 //   * S stages of LDS form a ring; a slab is requested S - 1 iterations before it is used.  One
 //     workgroup barrier per slab: before it every wavefront waits for ITS OWN requests of that slab
-//     (s_waitcnt vmcnt(n): loads complete in order, and every wavefront issues the same number per
-//     slab, the tail included, so n is a constant); after it the slab is visible to all, and the
-//     stage freed by the previous slab is requested again.
+//     (s_waitcnt vmcnt(n): loads complete in order and every wavefront issues the same number per
+//     slab, so n = the loads of the younger slabs still in flight); after it the slab is visible to
+//     all, and the stage freed by the previous slab is requested again.  The last S - 1 slabs
+//     request nothing (their n shrinks to 0).
 //   * LDS reads are issued from inline assembly and waited for with explicit lgkmcnt counts: the
 //     compiler cannot know which outstanding direct load an LDS read depends on and would otherwise
 //     drain all of them (vmcnt(0)) in front of every read, serialising the ring.
 //   * Epilogue as in the register-fed kernel (scale bits kept in two registers per thread through
-//     the loop and parked in LDS after it).
+//     the loop), with its LDS scratch in the S - 1 stages the last slab does not read: the scales
+//     are parked there just before the last slab's barrier, the wavefronts' strips follow them, and
+//     no wavefront waits for another between its last MFMA and its stores.
 #include <type_traits>
 
 #include "bwta_internal.h"
