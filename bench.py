@@ -507,8 +507,12 @@ def decode_cases(args, torch, B, synth, families=False):
     nmat = args.decode_matrices
     reps = max(20, args.decode_reps)
     res = []
+    only = getattr(args, "decode_only", None)  # "down:16:fp4": one shape, one token count, one kernel family
+    only = only.split(":") if only else None
     for which in ("upgate", "down"):
         for M in (1, 4, 16):
+            if only and (which != only[0] or M != int(only[1])):
+                continue
             c = synth.config4(which, M)
             L = Layer(c, torch, B, from_fp16=False)
             # distinct weight matrices: rotate the packed rows so the bits differ
@@ -529,14 +533,15 @@ def decode_cases(args, torch, B, synth, families=False):
                     B.set_path(B.PATH_AUTO)
                 return t[len(t) // 2] / nmat, t[0] / nmat
 
-            med, best = case(B.PATH_AUTO)
+            first = {"popc": B.PATH_POPC, "fp4": B.PATH_FP4}[only[2]] if only and len(only) > 2 else B.PATH_AUTO
+            med, best = case(first)
             bytes_ = L.gemm_bytes()
             r = dict(layer=c["name"], M=M, N=L.N, K=L.K, path=_kernel_path_name(B, L.M, L.N, L.K),
                      us_per_matrix_median=round(med * 1e3, 3), us_per_matrix_best=round(best * 1e3, 3),
                      GBs_median=round(bytes_ / (med * 1e-3) / 1e9, 1), GBs_best=round(bytes_ / (best * 1e-3) / 1e9, 1),
                      frac_hbm_median=round(bytes_ / (med * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                      algorithmic_bytes_per_matrix=bytes_)
-            if families:  # the other kernel family on the same case
+            if families and not only:  # the other kernel family on the same case
                 r["popc_us_median"] = round(case(B.PATH_POPC)[0] * 1e3, 3)
                 r["fp4_us_median"] = round(case(B.PATH_FP4)[0] * 1e3, 3)
                 r["single_launch_us"] = round(_event_ms(torch, lambda: L.gemm(B), args.steps, args.warmup) * 1e3, 2)
@@ -902,6 +907,8 @@ def main():
                              "short_k", "copy_probe"])
     ap.add_argument("--decode-matrices", type=int, default=64)
     ap.add_argument("--decode-reps", type=int, default=20, help="timed grouped launches per decode case (at least 20)")
+    ap.add_argument("--decode-only", default=None, metavar="SHAPE:M[:FAMILY]",
+                    help="c4_decode: one case only, e.g. down:16:fp4 (upgate|down, 1|4|16, popc|fp4); for counter runs")
     ap.add_argument("--no-sub", action="store_true", help="headline only: skip the c4 / c2 / c5 sub-records")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--graph", action="store_true",
