@@ -760,13 +760,20 @@ hipError_t launch_gemm_fp4(const GemmArgs &g, uint32_t *frag, bool frag_ready, h
     const int forced = g_fp4_tile.load(std::memory_order_relaxed);
     if ((forced == 223 || forced == 243 || forced == 323) && gemm_fp4_lds_supported(g))
         return launch_gemm_fp4_lds(g, frag, forced, st);
-    // Large products: both operands through LDS by direct loads, 128 x 256 tiles of 8 wavefronts.  Measured
-    // on the 7B shapes at 2048 tokens against the register-fed kernel below: 17.2 against 18.2 us
-    // (4096 -> 4096), 43.0 against 48.7 (4096 -> 11008), 39.7 against 43.3 (11008 -> 4096).  It needs about
-    // one tile per compute unit and a K loop long enough to pay for filling its ring.
-    if (forced == 0 && g.acc == nullptr && g.K >= 2048 && gemm_fp4_lds_supported(g) &&
-        (int64_t)((g.M + 127) / 128) * ((g.N + 255) / 256) >= 224)
-        return launch_gemm_fp4_lds(g, frag, 243, st);
+    // Large products: both operands through LDS by direct loads.  Measured against the register-fed
+    // kernel below on ready fragments (us, M x N x K): 128 x 256 tiles of 8 wavefronts win once there are
+    // about 160 of them and K is long enough to pay for filling the ring -- 2048 x 4096 x 4096 15.9 against
+    // 18.2, 2048 x 11008 x 4096 40.4 against 48.7, 2048 x 4096 x 11008 37.4 against 43.3, 512 x 11008 x 4096
+    // (172 tiles) 14.6 against 16.7, 8192 x 768 x 3072 (192) 12.1 against 13.8, 4096 x 4096 x 1024 12.6
+    // against 14.8; with fewer, 128 x 128 tiles of 4 wavefronts win where they come to about one per compute
+    // unit -- 1024 x 4096 x 4096 11.0 against 11.6, 512 x 8192 x 8192 17.7 against 19.0, 1024 x 4096 x 1024
+    // 6.2 against 6.7 -- and lose below that (512 x 4096 x 4096: 10.6 against 8.8).
+    if (forced == 0 && g.acc == nullptr && g.K >= 1024 && gemm_fp4_lds_supported(g)) {
+        const int64_t tm = (g.M + 127) / 128;
+        const int64_t tiles256 = tm * ((g.N + 255) / 256), tiles128 = tm * ((g.N + 127) / 128);
+        if (tiles256 >= (g.K >= 2048 ? 160 : 224)) return launch_gemm_fp4_lds(g, frag, 243, st);
+        if (tiles128 >= 224) return launch_gemm_fp4_lds(g, frag, 223, st);
+    }
     if (g.acc) return launch<2, 2, 2, 2, 2, true>(g, frag, s_pad, st);  // int32 output: test / debug path
     switch (forced) {  // forced tile (tuning sweeps); 0 = heuristic below
     case 22: return launch<2, 2, 2, 2, 2, false>(g, frag, s_pad, st);
