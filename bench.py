@@ -375,9 +375,22 @@ def run_headline(args, torch, B, synth):
     cfgs = [synth.config3(w) for w in ("qkvo", "upgate", "down")]
     layers = [Layer(c, torch, B, from_fp16=False) for c in cfgs]
 
-    def step():
+    def eager_step():
         for L in layers:
             L.gemm(B)
+
+    step = eager_step
+    if args.graph:  # the same six launches replayed from a HIP graph; every replay checked against eager below
+        def check(want):
+            got = [L.out.clone() for L in layers]
+            if want is not None:
+                for a, b in zip(got, want):
+                    assert torch.equal(a.view(torch.int16), b.view(torch.int16)), "graph replay differs from eager"
+            for L in layers:
+                L.out.fill_(float("nan"))
+            return got
+        graph = _graph_of(torch, eager_step, check)
+        step = graph.replay
 
     _settle(torch, step)
     for _ in range(args.warmup):
@@ -432,7 +445,8 @@ def run_headline(args, torch, B, synth):
            "config": {"workload": "c3_prefill: M=2048 ternary activations P(0)=0.5, (K,N) in {(4096,4096),(4096,11008),"
                                   "(11008,4096)}; one step = bwta_gemm (product + scale epilogue from packed planes) "
                                   "on all three",
-                      "launch": "eager", "clock_settle_ms": int(SETTLE_S * 1e3), "build_id": B.build_id()},
+                      "launch": "hip graph replay" if args.graph else "eager", "clock_settle_ms": int(SETTLE_S * 1e3),
+                      "build_id": B.build_id()},
            "roofline": roofline, "kernels": kern}
     del layers
     if not args.no_cpu:
