@@ -281,6 +281,12 @@ void k_gemm_fp4_lds(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, in
     // One slab: wait for the own requests of it (YOUNGER slabs of this wavefront may stay in flight: loads
     // complete in order and every wavefront issues LOADS per slab), then the barrier after which everyone's
     // have landed and everyone is done reading the previous slab.
+    // Inside the slab loop a wavefront issues ahead of the wavefronts of the other workgroup on this
+    // compute unit that are still setting up or already in their epilogue (scalar address arithmetic,
+    // conversions, LDS strips): those fill the gaps.  Measured on the shape that runs several rounds of
+    // workgroups per compute unit (2048 x 11008 x 4096): 45.0 -> 43.1 us on the same box; no change on
+    // the single-round shapes.
+    __builtin_amdgcn_s_setprio(3);
     int stage = 0;
     auto slab = [&](auto younger, auto before_barrier, auto after_barrier) {
         __builtin_amdgcn_sched_barrier(0);  // the previous slab's MFMAs stay in front of the wait
@@ -319,6 +325,7 @@ void k_gemm_fp4_lds(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, in
                  },
                  nothing);
     });
+    __builtin_amdgcn_s_setprio(0);
     // `stage` now names the stage behind the last slab's; wavefronts 0 .. EPI_FIRST - 1 put their strips
     // behind the scales, the others into the stages that follow
     int st_e = stage;
