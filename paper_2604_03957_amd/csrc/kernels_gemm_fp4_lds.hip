@@ -278,9 +278,6 @@ void k_gemm_fp4_lds(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, in
     const uint32_t a_rd = lds0 + (uint32_t)((wm * WM) * 4096 + lane * 16);                          // + i 4096 + step 1024
     const uint32_t w_rd = lds0 + (uint32_t)(C::A_BYTES + (wn * WN) * 1024 + r32 * 16 + h * 8);      // + j 1024 (+ 512: steps 2, 3)
 
-    // One slab: wait for the own requests of it (YOUNGER slabs of this wavefront may stay in flight: loads
-    // complete in order and every wavefront issues LOADS per slab), then the barrier after which everyone's
-    // have landed and everyone is done reading the previous slab.
     // Inside the slab loop a wavefront issues ahead of the wavefronts of the other workgroup on this
     // compute unit that are still setting up or already in their epilogue (scalar address arithmetic,
     // conversions, LDS strips): those fill the gaps.  Measured on the shape that runs several rounds of
@@ -288,6 +285,9 @@ void k_gemm_fp4_lds(GemmArgs g, const uint32_t *__restrict__ frag, int s_pad, in
     // the single-round shapes.
     __builtin_amdgcn_s_setprio(3);
     int stage = 0;
+    // One slab: wait for the own requests of it (YOUNGER slabs of this wavefront may stay in flight: loads
+    // complete in order and every wavefront issues LOADS per slab), then the barrier after which everyone's
+    // have landed and everyone is done reading the previous slab.
     auto slab = [&](auto younger, auto before_barrier, auto after_barrier) {
         __builtin_amdgcn_sched_barrier(0);  // the previous slab's MFMAs stay in front of the wait
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(decltype(younger)::value * C::LOADS) : "memory");
